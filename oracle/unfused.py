@@ -1,0 +1,313 @@
+"""Operator-at-a-time evaluation of template expressions -- TEST INFRASTRUCTURE ONLY.
+
+A fused operator computes exactly what the chain of basic operators it replaces
+computes (Sec. 1, "Fusion Opportunities": fusion removes intermediates and
+scans, not arithmetic).  So the reference result of an expression is the plain
+definition: walk the postfix expression, execute ONE basic operator of
+``oracle.ops`` per token over whole matrices, and materialise every
+intermediate -- the paper's "Base" plan (Sec. 5.1).
+
+Expressions are symbolic postfix lists of tuples:
+    ("main",)            the template's main input X (cell / row / stored cell)
+    ("side", k)          side input k (Table 1: the list Y of side inputs)
+    ("const", c)         literal scalar
+    ("uvdot",)           Outer only: U[i,:] . V[j,:] at the stored cell (i, j)
+    (name,)              element-wise unary / binary operator, see ``oracle.ops``
+    ("rowsum",)          Row only: sum over the columns of a row vector
+    ("dot",)             Row only: inner product of two row vectors
+Side inputs are ``(kind, array)`` pairs with kind in
+    "matrix" (m x n), "colvec" (m, indexed by row), "rowvec" (n, indexed by
+    column), "scalar".
+Aggregation variants (Table 1): "none", "full", "row", "col", "col_t".
+"""
+import numpy as np
+
+from . import ops
+
+_ZERO_PRESERVING_UNARY = {"neg", "abs", "sqrt", "pow2", "sign", "neq0"}
+
+
+def _side_dense(kind, arr, m, n):
+    """Side input as an array that broadcasts against an m x n matrix."""
+    a = np.asarray(arr, dtype=np.float64)
+    if kind == "matrix":
+        assert a.shape == (m, n), (a.shape, (m, n))
+        return a
+    if kind == "colvec":
+        assert a.size == m
+        return a.reshape(m, 1)
+    if kind == "rowvec":
+        assert a.size == n
+        return a.reshape(1, n)
+    if kind == "scalar":
+        assert a.size == 1
+        return a.reshape(())
+    raise ValueError("unknown side kind %r" % (kind,))
+
+
+def _aggregate_dense(r, m, n, agg):
+    """Apply a Table-1 aggregation variant to a (broadcastable) m x n result."""
+    full = np.array(np.broadcast_to(r, (m, n)), dtype=np.float64)   # materialise
+    if agg == "none":
+        return full
+    if agg == "full":
+        return np.array([ops.sum_full(full)])
+    if agg == "row":
+        return ops.row_sums(full) if n > 0 else np.zeros(m)
+    if agg in ("col", "col_t"):
+        return ops.col_sums(full) if m > 0 else np.zeros(n)
+    raise ValueError("unknown aggregation %r" % (agg,))
+
+
+# ---------------------------------------------------------------- Cell, MAgg ---
+
+def _eval_cells(expr, x, sides):
+    m, n = x.shape
+    st = []
+    for tok in expr:
+        name = tok[0]
+        if name == "main":
+            st.append(x)
+        elif name == "side":
+            kind, arr = sides[tok[1]]
+            st.append(_side_dense(kind, arr, m, n))
+        elif name == "const":
+            st.append(np.float64(tok[1]))
+        elif name in ops.UNARY_NAMES:
+            a = st.pop()
+            st.append(ops.ew_unary(name, a))
+        elif name in ops.BINARY_NAMES:
+            b = st.pop()
+            a = st.pop()
+            st.append(ops.ew_binary(name, a, b))
+        else:
+            raise ValueError("token %r is not valid in a Cell expression" % (tok,))
+    if len(st) != 1:
+        raise ValueError("expression leaves %d values on the stack" % len(st))
+    return st[0]
+
+
+def cell(expr, x, sides, agg):
+    """Cell template (Table 1; Sec. 2.2 Cell listing): per-cell chain over dense X,
+    then the aggregation variant.  Returns a float64 array (shape by variant)."""
+    x = np.asarray(x, dtype=np.float64)
+    m, n = x.shape
+    return _aggregate_dense(_eval_cells(expr, x, sides), m, n, agg)
+
+
+def magg(exprs, x, sides):
+    """MAgg template (Table 1; Fig. 1c; Sec. 5.2 "Multi-Aggregate Operations"):
+    k full aggregates, each computed on its own, unfused; returns k values."""
+    return np.array([cell(e, x, sides, "full")[0] for e in exprs])
+
+
+# ----------------------------------------------------------------------- Row ---
+
+def row_dense(expr, x, sides, agg):
+    """Row template over a dense main input (Table 1; Sec. 2.2 Row listing).
+
+    Values are row vectors ("V": broadcastable to m x n) or per-row scalars
+    ("S": shape (m,1) or ()).  Returns an array shaped by the variant:
+    none -> m x n (V) or m (S); row -> m; col / col_t -> n; full -> 1.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    m, n = x.shape
+    st = []   # (kind, array)
+    for tok in expr:
+        name = tok[0]
+        if name == "main":
+            st.append(("V", x))
+        elif name == "side":
+            kind, arr = sides[tok[1]]
+            a = _side_dense(kind, arr, m, n)
+            st.append(("V" if kind in ("matrix", "rowvec") else "S", a))
+        elif name == "const":
+            st.append(("S", np.float64(tok[1])))
+        elif name in ops.UNARY_NAMES:
+            k, a = st.pop()
+            st.append((k, ops.ew_unary(name, a)))
+        elif name in ops.BINARY_NAMES:
+            kb, b = st.pop()
+            ka, a = st.pop()
+            st.append(("V" if "V" in (ka, kb) else "S", ops.ew_binary(name, a, b)))
+        elif name == "rowsum":
+            k, a = st.pop()
+            if k != "V":
+                raise ValueError("rowsum of a scalar")
+            full = np.array(np.broadcast_to(a, (m, n)))
+            st.append(("S", ops.row_sums(full).reshape(m, 1)))
+        elif name == "dot":
+            kb, b = st.pop()
+            ka, a = st.pop()
+            if ka != "V" or kb != "V":
+                raise ValueError("dot needs two row vectors")
+            t = np.array(np.broadcast_to(ops.ew_binary("mul", a, b), (m, n)))
+            st.append(("S", ops.row_sums(t).reshape(m, 1)))
+        else:
+            raise ValueError("token %r is not valid in a Row expression" % (tok,))
+    if len(st) != 1:
+        raise ValueError("expression leaves %d values on the stack" % len(st))
+    kind, r = st[0]
+    if kind == "V":
+        return _aggregate_dense(r, m, n, agg)
+    per_row = np.array(np.broadcast_to(np.asarray(r).reshape(-1, 1) if np.ndim(r) else r, (m, 1)),
+                       dtype=np.float64).reshape(m)
+    if agg == "none":
+        return per_row
+    if agg == "full":
+        return np.array([ops.sum_full(per_row)])
+    raise ValueError("aggregation %r needs a row-vector result" % (agg,))
+
+
+def row_csr(expr, x: ops.Csr, sides, agg):
+    """Row template over a CSR main input: the sparse-safe binding (Sec. 2.2
+    "Template Types": a sparse-safe template binds only to the non-zeros).
+
+    Row-vector values are carried on X's pattern (one value per stored cell); a
+    value is usable that way only if it is zero wherever X has no stored cell,
+    which is tracked per value.  Dense-valued vectors (side inputs) are gathered
+    at the stored positions and may only be consumed by an operator that makes
+    the result zero-preserving again (e.g. multiply with X).  Programs that are
+    not sparse-safe raise ValueError.
+    Returns: none -> nnz-vector on X's pattern (V) or m (S); row -> m;
+    col / col_t -> n; full -> 1.
+    """
+    m, n = x.shape
+    rows = ops.csr_row_index(x)
+    st = []   # ("V", nnz-array, zero_preserving) | ("S", array (m,) or 0-d)
+
+    def expand(k, a):      # per-row scalar -> per stored cell
+        a = np.asarray(a, dtype=np.float64)
+        return a if (k == "V" or a.ndim == 0) else a[rows]
+
+    for tok in expr:
+        name = tok[0]
+        if name == "main":
+            st.append(("V", x.vals, True))
+        elif name == "side":
+            kind, arr = sides[tok[1]]
+            a = np.asarray(arr, dtype=np.float64)
+            if kind == "matrix":
+                assert a.shape == (m, n)
+                st.append(("V", a[rows, x.colidx], False))
+            elif kind == "rowvec":
+                assert a.size == n
+                st.append(("V", a.reshape(-1)[x.colidx], False))
+            elif kind == "colvec":
+                assert a.size == m
+                st.append(("S", a.reshape(m), None))
+            elif kind == "scalar":
+                st.append(("S", a.reshape(()), None))
+            else:
+                raise ValueError(kind)
+        elif name == "const":
+            st.append(("S", np.float64(tok[1]), None))
+        elif name in ops.UNARY_NAMES:
+            k, a, z = st.pop()
+            zz = (z and name in _ZERO_PRESERVING_UNARY) if k == "V" else None
+            st.append((k, ops.ew_unary(name, a), zz))
+        elif name in ops.BINARY_NAMES:
+            kb, b, zb = st.pop()
+            ka, a, za = st.pop()
+            if ka == "S" and kb == "S":
+                st.append(("S", ops.ew_binary(name, a, b), None))
+                continue
+            if name == "mul":
+                z = bool(za) or bool(zb)
+            elif name in ("add", "sub"):
+                z = ka == "V" and kb == "V" and za and zb
+            elif name == "div":
+                z = ka == "V" and bool(za)
+            else:
+                z = False
+            st.append(("V", ops.ew_binary(name, expand(ka, a), expand(kb, b)), z))
+        elif name in ("rowsum", "dot"):
+            if name == "dot":
+                kb, b, zb = st.pop()
+                ka, a, za = st.pop()
+                if ka != "V" or kb != "V":
+                    raise ValueError("dot needs two row vectors")
+                a, z, k = ops.ew_binary("mul", a, b), bool(za) or bool(zb), "V"
+            else:
+                k, a, z = st.pop()
+            if k != "V":
+                raise ValueError("rowsum of a scalar")
+            if not z:
+                raise ValueError("not sparse-safe: row aggregate of a dense-valued vector")
+            st.append(("S", ops.csr_row_sums(x, a), None))
+        else:
+            raise ValueError("token %r is not valid in a Row expression" % (tok,))
+    if len(st) != 1:
+        raise ValueError("expression leaves %d values on the stack" % len(st))
+    kind, r, z = st[0]
+    if kind == "S":
+        per_row = np.array(np.broadcast_to(r, (m,)), dtype=np.float64)
+        if agg == "none":
+            return per_row
+        if agg == "full":
+            return np.array([ops.sum_full(per_row)])
+        raise ValueError("aggregation %r needs a row-vector result" % (agg,))
+    if not z:
+        raise ValueError("not sparse-safe: result is not zero where X is zero")
+    r = np.array(np.broadcast_to(r, x.vals.shape), dtype=np.float64)
+    if agg == "none":
+        return r
+    if agg == "full":
+        return np.array([ops.sum_full(r)])
+    if agg == "row":
+        return ops.csr_row_sums(x, r)
+    if agg in ("col", "col_t"):
+        return ops.csr_col_sums(x, r)
+    raise ValueError("unknown aggregation %r" % (agg,))
+
+
+# --------------------------------------------------------------------- Outer ---
+
+def outer(expr, x: ops.Csr, u, v, sides, agg):
+    """Outer template (Table 1; Sec. 2.2 Outer listing and the paragraph after
+    it): binds to every stored cell X_ij, the rows U_i and V_j and dense side
+    inputs; the chain is evaluated over nnz-vectors, never over m x n.
+
+    agg "full" -> 1 value; "none" -> nnz-vector on X's pattern.
+    """
+    m, n = x.shape
+    rows = ops.csr_row_index(x)
+    st = []
+    for tok in expr:
+        name = tok[0]
+        if name == "main":
+            st.append(x.vals)
+        elif name == "uvdot":
+            st.append(ops.csr_uv_dot(x, u, v))
+        elif name == "side":
+            kind, arr = sides[tok[1]]
+            a = np.asarray(arr, dtype=np.float64)
+            if kind == "matrix":
+                assert a.shape == (m, n)
+                st.append(a[rows, x.colidx])
+            elif kind == "colvec":
+                st.append(a.reshape(m)[rows])
+            elif kind == "rowvec":
+                st.append(a.reshape(n)[x.colidx])
+            elif kind == "scalar":
+                st.append(a.reshape(()))
+            else:
+                raise ValueError(kind)
+        elif name == "const":
+            st.append(np.float64(tok[1]))
+        elif name in ops.UNARY_NAMES:
+            st.append(ops.ew_unary(name, st.pop()))
+        elif name in ops.BINARY_NAMES:
+            b = st.pop()
+            a = st.pop()
+            st.append(ops.ew_binary(name, a, b))
+        else:
+            raise ValueError("token %r is not valid in an Outer expression" % (tok,))
+    if len(st) != 1:
+        raise ValueError("expression leaves %d values on the stack" % len(st))
+    r = np.array(np.broadcast_to(st[0], x.vals.shape), dtype=np.float64)
+    if agg == "none":
+        return r
+    if agg == "full":
+        return np.array([ops.sum_full(r)])
+    raise ValueError("unknown aggregation %r" % (agg,))
