@@ -1,0 +1,237 @@
+/*
+ * libfuse -- execution of generated fused operators on MI355X (gfx950).
+ *
+ * One entry point per fusion template of the paper (Table 1, "CPlan Template
+ * Types and their Variants"): Cell, MAgg, Row and Outer.  A fused operator is
+ * a template skeleton (data access, parallelisation, aggregation: hand-written
+ * HIP) plus a generated body (Sec. 2.2, "Runtime Integration": the skeleton
+ * calls `genexec` per cell / row / non-zero).  Here the body is given as a
+ * postfix expression descriptor (the analogue of a CPlan, Sec. 2.2 "Code
+ * Generation Plans"), turned into HIP source, compiled with hipRTC and kept in
+ * a plan cache keyed by the descriptor (Sec. 2.1 "Codegen Architecture": equal
+ * CPlans are compiled once).
+ *
+ * Conventions for every call
+ *   - All `data`, `vals`, `colidx`, `rowptr` and `out` pointers are DEVICE
+ *     pointers owned by the caller; libfuse never frees or reallocates them and
+ *     never copies them to the host.  Descriptor structs (`fuse_expr`,
+ *     `fuse_tok`, `fuse_dense`, `fuse_csr`, `fuse_side`) live in HOST memory and
+ *     are only read during the call.
+ *   - Matrices are fp64 (the paper's precision, Sec. 5.1 "Baselines"),
+ *     row-major with a leading dimension `ld` >= cols counted in elements.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  A call
+ *     enqueues its kernel(s) on that stream and returns without synchronising;
+ *     results are in `out` once the stream reaches that point.  The first call
+ *     with a new descriptor compiles it (hipRTC, host-side, blocking).
+ *   - libfuse owns a small per-(device, stream) workspace for block partials;
+ *     two calls that overlap on the same stream handle from different host
+ *     threads are not supported.
+ *   - Return value: FUSE_OK (0) or a negative fuse_status; on error nothing is
+ *     enqueued and `fuse_last_error()` returns a thread-local message
+ *     (including the hipRTC log for FUSE_ECOMPILE).
+ *   - The only aggregation function is sum (the one the paper's operators in
+ *     Sec. 5.2 use).  Sums are accumulated in fp64 in an unspecified but
+ *     run-to-run deterministic order, except where noted.
+ */
+#ifndef LIBFUSE_FUSE_H
+#define LIBFUSE_FUSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FUSE_OK = 0,
+    FUSE_EINVAL = -1,       /* NULL pointer, negative size, bad enum value            */
+    FUSE_ESHAPE = -2,       /* operand shapes do not match                            */
+    FUSE_EDESC = -3,        /* malformed expression (stack, kinds, sparse-safety)     */
+    FUSE_ECOMPILE = -4,     /* hipRTC rejected the generated source                   */
+    FUSE_ERUNTIME = -5,     /* a HIP runtime call failed                              */
+    FUSE_ENOMEM = -6,       /* workspace allocation failed                            */
+    FUSE_EUNSUPPORTED = -7  /* valid request that this build does not implement       */
+} fuse_status;
+
+/* Aggregation variants of Table 1.  COL and COL_T produce the same n values
+ * (column sums); they differ only in the logical shape (1 x n vs n x 1). */
+typedef enum {
+    FUSE_AGG_NONE = 0,
+    FUSE_AGG_FULL = 1,
+    FUSE_AGG_ROW = 2,
+    FUSE_AGG_COL = 3,
+    FUSE_AGG_COL_T = 4
+} fuse_agg;
+
+/* How a side input is addressed from cell (rix, cix) of the main input
+ * (Sec. 2.2, Cell listing: getValue(b[k], n, rix, cix) and getValue(b[k], rix)). */
+typedef enum {
+    FUSE_SIDE_MATRIX = 0,   /* rows x cols as the main input, value at (rix, cix)     */
+    FUSE_SIDE_COLVEC = 1,   /* `rows` values, value at rix  (data[rix * ld])          */
+    FUSE_SIDE_ROWVEC = 2,   /* `cols` values, value at cix  (data[cix], contiguous)   */
+    FUSE_SIDE_SCALAR = 3    /* host scalar in `scalar`; passed as a kernel argument   */
+} fuse_side_kind;
+
+typedef struct {
+    const double *data;     /* device pointer                                         */
+    int64_t rows, cols;
+    int64_t ld;             /* leading dimension in elements, >= cols                 */
+} fuse_dense;
+
+/* CSR with sorted, distinct column indices per row.  Every STORED entry is
+ * processed, whatever its value (Table 1: the binding is to the stored cells). */
+typedef struct {
+    const double *vals;     /* device, nnz values                                     */
+    const int32_t *colidx;  /* device, nnz column indices in [0, cols)                */
+    const void *rowptr;     /* device, rows+1 offsets, int32 or int64                 */
+    int32_t rowptr_is64;    /* 0: int32 offsets (nnz < 2^31), 1: int64                */
+    int64_t rows, cols;
+    int64_t nnz;            /* must equal rowptr[rows]                                */
+} fuse_csr;
+
+typedef struct {
+    int32_t kind;           /* fuse_side_kind                                         */
+    fuse_dense m;           /* MATRIX: rows x cols, ld; COLVEC: rows x 1, ld = stride
+                               between consecutive rows' values; ROWVEC: 1 x cols     */
+    double scalar;          /* SCALAR only                                            */
+} fuse_side;
+
+/* Postfix expression tokens. */
+typedef enum {
+    /* leaves */
+    FUSE_OP_MAIN = 1,       /* the main input: cell value / row vector / non-zero     */
+    FUSE_OP_SIDE = 2,       /* side input number `arg`                                */
+    FUSE_OP_CONST = 3,      /* literal `imm` (compiled into the body)                 */
+    FUSE_OP_UVDOT = 4,      /* Outer only: U[i,:] . V[j,:] at the non-zero (i, j)     */
+    /* element-wise unary */
+    FUSE_OP_NEG = 16, FUSE_OP_ABS, FUSE_OP_SQRT, FUSE_OP_EXP, FUSE_OP_LOG,
+    FUSE_OP_POW2,           /* x * x                                                  */
+    FUSE_OP_SIGN,           /* -1, 0, +1                                              */
+    FUSE_OP_NEQ0,           /* x != 0 ? 1 : 0  (Sec. 2.2, Outer listing)              */
+    FUSE_OP_SIGMOID,        /* 1 / (1 + exp(-x))                                      */
+    /* element-wise binary: pops b, then a; pushes a (op) b */
+    FUSE_OP_ADD = 32, FUSE_OP_SUB, FUSE_OP_MUL, FUSE_OP_DIV, FUSE_OP_MIN, FUSE_OP_MAX,
+    FUSE_OP_POW,
+    FUSE_OP_LT, FUSE_OP_LE, FUSE_OP_GT, FUSE_OP_GE, FUSE_OP_EQ, FUSE_OP_NE, /* 1.0 / 0.0 */
+    /* Row template only: row vector -> per-row scalar */
+    FUSE_OP_ROWSUM = 48,    /* sum over the columns of a row vector  (vectSum)        */
+    FUSE_OP_DOT = 49        /* inner product of two row vectors      (dotProduct)     */
+} fuse_op;
+
+typedef struct {
+    int32_t op;             /* fuse_op                                                */
+    int32_t arg;            /* FUSE_OP_SIDE: index into `sides`; else 0               */
+    double imm;             /* FUSE_OP_CONST: the literal; else 0                     */
+} fuse_tok;
+
+typedef struct {
+    const fuse_tok *toks;   /* host pointer                                           */
+    int32_t ntoks;
+} fuse_expr;
+
+/* --------------------------------------------------------------------------
+ * Cell template (Table 1, row "Cell"; Sec. 2.2 Cell listing; Fig. 1a / Fig. 8a
+ * sum(X*Y*Z)).  The body is a scalar expression evaluated at every cell
+ * (rix, cix) of the dense main input X; side inputs are read at the same cell.
+ *   agg NONE : out[rix * X->cols + cix] = body          (m*n values, dense, ld = cols)
+ *   agg ROW  : out[rix] = sum over cix                  (m values)
+ *   agg COL / COL_T : out[cix] = sum over rix           (n values)
+ *   agg FULL : out[0] = sum over all cells              (1 value)
+ * Shape rules: MATRIX sides m x n, COLVEC m, ROWVEC n.  Empty inputs give zero
+ * sums.  Row tokens (ROWSUM, DOT) and UVDOT are FUSE_EDESC.
+ */
+int fuse_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_side *sides, int nsides,
+              int agg, double *out, void *stream);
+
+/* MAgg template (Table 1, row "MAgg"; Fig. 1c; Sec. 5.2 "Multi-Aggregate
+ * Operations"): k full aggregates over shared inputs in ONE scan of X and the
+ * side inputs.  exprs[0..k) are Cell bodies; out_k[j] = sum over all cells of
+ * body j (the k x 1 output).  1 <= k <= 16. */
+int fuse_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides,
+              int nsides, double *out_k, void *stream);
+
+/* Row template (Table 1, row "Row"; Sec. 2.2 Row listing; Fig. 1b / Fig. 8e-f
+ * t(X) %*% (X %*% v)).  The body runs once per row of the main input, dense
+ * (Xd) or CSR (Xs) -- exactly one of the two is non-NULL.  Values in the body
+ * are row vectors (MAIN, MATRIX and ROWVEC sides) or per-row scalars (COLVEC
+ * and SCALAR sides, constants, results of ROWSUM / DOT); binary operators
+ * broadcast a scalar over a vector.
+ *   vector result:  NONE -> out is m x n dense (Xd) or nnz values on X's pattern
+ *                   (Xs); ROW -> m row sums; COL / COL_T -> n column sums
+ *                   (t(X) %*% q is the body `X_i * q_i` with COL_T); FULL -> 1.
+ *   scalar result:  NONE -> m values; FULL -> 1; others FUSE_EDESC.
+ * For CSR input the body must be sparse-safe (Sec. 2.2 "Template Types": a
+ * sparse-safe template binds only to the non-zeros): every vector that is
+ * aggregated or returned must be zero wherever X has no stored cell (products
+ * with X, zero-preserving unaries, sums of such); otherwise FUSE_EDESC.
+ * With CSR input and COL / COL_T the order in which a block's rows are added
+ * to a column sum is not fixed (shared-memory atomics); all else is deterministic.
+ * Limits of this build: vector results / ROWSUM / DOT need cols <= 2048 for
+ * dense input (FUSE_EUNSUPPORTED beyond); CSR with COL / COL_T needs
+ * cols <= 6144.
+ */
+int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
+             const fuse_side *sides, int nsides, int agg, double *out, void *stream);
+
+/* Outer template (Table 1, row "Outer"; Sec. 2.2 Outer listing and the
+ * paragraph after it; Fig. 1d / Fig. 8h sum(X * log(U %*% t(V) + eps))).
+ * The body is a scalar expression evaluated at every stored cell (i, j) of
+ * the CSR matrix X with MAIN = X_ij and UVDOT = U[i,:] . V[j,:]; U is
+ * X->rows x r, V is X->cols x r; U %*% t(V) is never formed.  Side inputs are
+ * dense and read at (i, j) / i / j.
+ *   agg FULL : out[0] = sum over stored cells of body
+ *   agg NONE : out[p] = body at stored cell p (nnz values on X's pattern)
+ * 1 <= r <= 1024. */
+int fuse_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
+               const fuse_side *sides, int nsides, int agg, double *out, void *stream);
+
+/* Validate a request and compile its body into the plan cache without
+ * launching anything (no device needed: the target is FUSE_ARCH, default
+ * gfx950, when no GPU is present).  Same arguments and errors as the calls
+ * above; data pointers may be NULL, only shapes, `ld`, kinds and the
+ * expression are used (alignment is assumed to be 16 bytes). */
+int fuse_prepare_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_side *sides,
+                      int nsides, int agg);
+int fuse_prepare_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides,
+                      int nsides);
+int fuse_prepare_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
+                     const fuse_side *sides, int nsides, int agg);
+int fuse_prepare_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U,
+                       const fuse_dense *V, const fuse_side *sides, int nsides, int agg);
+
+/* Message of the calling thread's last failed call ("" if none).  The pointer
+ * stays valid until that thread's next libfuse call. */
+const char *fuse_last_error(void);
+
+/* Plan-cache counters since load / last clear: lookups that found a compiled
+ * body, lookups that compiled one, and total hipRTC milliseconds.  Any pointer
+ * may be NULL. */
+int fuse_cache_stats(int64_t *hits, int64_t *misses, double *compile_ms);
+
+/* Drop every compiled body and free the workspaces.  The caller must have
+ * synchronised all streams that libfuse work was enqueued on. */
+void fuse_cache_clear(void);
+
+/* Copy the HIP source generated for the most recent plan-cache miss of the
+ * calling thread into buf (NUL-terminated, truncated to buflen); returns the
+ * full length.  For inspection and tests. */
+size_t fuse_last_source(char *buf, size_t buflen);
+
+/* Name of the kernel that the most recent successful fuse_* / fuse_prepare_*
+ * call of the calling thread launched or compiled (as a profiler shows it). */
+const char *fuse_last_kernel(void);
+
+/* Measurement helpers (statically compiled kernels, not part of the paper's
+ * method): a plain device-to-device copy and a read-only pass over n_doubles
+ * fp64 values (n_doubles even, pointers 16-byte aligned), launched with
+ * `blocks` blocks of 256 threads on `stream`.  They give the achievable HBM
+ * ceiling and calibrate profiler byte counters against a known transfer.
+ * `sink` is one device double that is practically never written. */
+int fuse_probe_copy(double *dst, const double *src, int64_t n_doubles, int blocks, void *stream);
+int fuse_probe_read(const double *src, int64_t n_doubles, int blocks, double *sink, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LIBFUSE_FUSE_H */

@@ -1,0 +1,10 @@
+"""Python binding of libfuse: fused-operator templates (Cell, MAgg, Row, Outer) on MI355X.
+
+Only argument marshalling happens here; every step of a call runs in the HIP
+kernels of ``libfuse.so`` (see ``include/fuse.h``).  PyTorch is used for device
+memory and streams.
+"""
+from .api import (FuseError, Csr, fuse_cell, fuse_magg, fuse_row, fuse_outer,  # noqa: F401
+                  prepare_cell, prepare_magg, prepare_row, prepare_outer,
+                  cache_stats, cache_clear, last_source, last_kernel, probe_copy, probe_read,
+                  AGG, SIDE, OPS, lib_path)

@@ -1,0 +1,306 @@
+"""Thin wrappers with the names of the C entry points (argument marshalling only)."""
+import ctypes
+from collections import namedtuple
+
+from . import _lib as L
+
+AGG = {"none": 0, "full": 1, "row": 2, "col": 3, "col_t": 4}
+SIDE = {"matrix": 0, "colvec": 1, "rowvec": 2, "scalar": 3}
+OPS = {
+    "main": 1, "side": 2, "const": 3, "uvdot": 4,
+    "neg": 16, "abs": 17, "sqrt": 18, "exp": 19, "log": 20, "pow2": 21, "sign": 22, "neq0": 23,
+    "sigmoid": 24,
+    "add": 32, "sub": 33, "mul": 34, "div": 35, "min": 36, "max": 37, "pow": 38,
+    "lt": 39, "le": 40, "gt": 41, "ge": 42, "eq": 43, "ne": 44,
+    "rowsum": 48, "dot": 49,
+}
+
+Csr = namedtuple("Csr", "rowptr colidx vals shape")
+"""CSR matrix on the device: rowptr (int32 or int64, m+1), colidx (int32), vals (float64), (m, n)."""
+
+
+class FuseError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("libfuse error %d: %s" % (code, msg))
+        self.code = code
+
+
+def lib_path():
+    return L.LIB_PATH
+
+
+def _check(rc):
+    if rc != 0:
+        raise FuseError(rc, L.load().fuse_last_error().decode("utf-8", "replace"))
+
+
+def _expr(tokens):
+    """Symbolic postfix list, e.g. [("main",), ("side", 0), ("mul",)] -> (Expr, keep-alive)."""
+    arr = (L.Tok * max(len(tokens), 1))()
+    for i, t in enumerate(tokens):
+        name = t[0]
+        if name not in OPS:
+            raise ValueError("unknown token %r" % (t,))
+        arr[i].op = OPS[name]
+        arr[i].arg = int(t[1]) if name == "side" else 0
+        arr[i].imm = float(t[1]) if name == "const" else 0.0
+    return L.Expr(arr, len(tokens)), arr
+
+
+def _dense(t, rows=None, cols=None):
+    """2-D (or 1-D) float64 tensor with unit column stride -> Dense descriptor."""
+    import torch
+    if t is None:
+        return None
+    if isinstance(t, tuple):                      # shape only (prepare_*): (rows, cols[, ld])
+        r, c = int(t[0]), int(t[1])
+        return L.Dense(None, r, c, int(t[2]) if len(t) > 2 else max(c, 1))
+    if t.dtype != torch.float64:
+        raise TypeError("libfuse matrices are float64")
+    if t.dim() == 1:
+        t = t.view(-1, 1) if cols == 1 else t.view(1, -1)
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("need a 2-D tensor with unit column stride")
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+    if t.shape[1] == 1 and t.shape[0] > 1:
+        ld = t.stride(0)
+    return L.Dense(t.data_ptr(), t.shape[0], t.shape[1], max(int(ld), 1))
+
+
+def _sides(sides, m, n):
+    """[(kind, tensor | float | shape-tuple)] -> (Side array, count)."""
+    arr = (L.Side * max(len(sides), 1))()
+    for k, (kind, val) in enumerate(sides):
+        arr[k].kind = SIDE[kind]
+        if kind == "scalar":
+            arr[k].scalar = float(val)
+        elif kind == "colvec":
+            if isinstance(val, tuple) or val is None:
+                arr[k].m = L.Dense(None, m, 1, 1)
+            else:
+                v = val.view(-1, 1) if val.dim() == 1 else val
+                arr[k].m = L.Dense(v.data_ptr(), v.shape[0], 1, max(int(v.stride(0)), 1))
+        elif kind == "rowvec":
+            if isinstance(val, tuple) or val is None:
+                arr[k].m = L.Dense(None, 1, n, max(n, 1))
+            else:
+                v = val.reshape(1, -1) if val.dim() == 1 else val
+                if v.shape[0] != 1 and v.shape[1] == 1:      # an n x 1 column used by column index
+                    if v.stride(0) != 1:
+                        raise ValueError("row-vector side must be contiguous")
+                    v = v.view(1, -1)
+                if v.shape[1] > 1 and v.stride(1) != 1:
+                    raise ValueError("row-vector side must be contiguous")
+                arr[k].m = L.Dense(v.data_ptr(), 1, v.shape[1], max(v.shape[1], 1))
+        else:
+            arr[k].m = _dense(val if val is not None else (m, n))
+    return arr, len(sides)
+
+
+def _csr(x):
+    import torch
+    rowptr, colidx, vals, shape = x
+    m, n = int(shape[0]), int(shape[1])
+    if isinstance(rowptr, int):                   # prepare_*: (is64, None, nnz, shape)
+        return L.CsrDesc(None, None, None, int(rowptr), m, n, int(vals))
+    if colidx.dtype != torch.int32 or vals.dtype != torch.float64:
+        raise TypeError("CSR needs int32 column indices and float64 values")
+    if rowptr.dtype not in (torch.int32, torch.int64):
+        raise TypeError("CSR row offsets must be int32 or int64")
+    if not (rowptr.is_contiguous() and colidx.is_contiguous() and vals.is_contiguous()):
+        raise ValueError("CSR arrays must be contiguous")
+    if rowptr.numel() != m + 1 or colidx.numel() != vals.numel():
+        raise ValueError("CSR array lengths do not match the shape")
+    return L.CsrDesc(vals.data_ptr(), colidx.data_ptr(), rowptr.data_ptr(),
+                     1 if rowptr.dtype == torch.int64 else 0, m, n, vals.numel())
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _out(out, count, like):
+    import torch
+    if out is None:
+        out = torch.empty(int(count), dtype=torch.float64, device=like.device)
+    elif out.dtype != torch.float64 or not out.is_contiguous() or out.numel() < count:
+        raise ValueError("out must be a contiguous float64 tensor with at least %d elements" % count)
+    return out
+
+
+def _agg_count(agg, m, n, vec_result=True, nnz=None):
+    if agg == "full":
+        return 1
+    if agg == "row":
+        return m
+    if agg in ("col", "col_t"):
+        return n
+    if nnz is not None and vec_result:
+        return nnz
+    return m * n if vec_result else m
+
+
+# --------------------------------------------------------------------- entry points ---
+
+def fuse_cell(expr, X, sides=(), agg="full", out=None, stream=None):
+    """C: fuse_cell.  X: cuda float64 (m, n).  Returns the out tensor (flat)."""
+    lib = L.load()
+    e, keep = _expr(expr)
+    xd = _dense(X)
+    sa, ns = _sides(list(sides), xd.rows, xd.cols)
+    out = _out(out, _agg_count(agg, xd.rows, xd.cols), X)
+    _check(lib.fuse_cell(ctypes.byref(e), ctypes.byref(xd), sa, ns, AGG[agg], out.data_ptr(), _stream(stream)))
+    return out
+
+
+def fuse_magg(exprs, X, sides=(), out=None, stream=None):
+    """C: fuse_magg.  k full aggregates in one scan; returns k values."""
+    lib = L.load()
+    pairs = [_expr(e) for e in exprs]
+    ea = (L.Expr * len(pairs))(*[p[0] for p in pairs])
+    xd = _dense(X)
+    sa, ns = _sides(list(sides), xd.rows, xd.cols)
+    out = _out(out, len(pairs), X)
+    _check(lib.fuse_magg(ea, len(pairs), ctypes.byref(xd), sa, ns, out.data_ptr(), _stream(stream)))
+    return out
+
+
+def _row_result_is_vector(expr, sides):
+    """Kind of a Row body's result (only used to size the output of agg='none')."""
+    st = []
+    for t in expr:
+        name = t[0]
+        if name == "main":
+            st.append(True)
+        elif name == "side":
+            st.append(sides[t[1]][0] in ("matrix", "rowvec"))
+        elif name == "const":
+            st.append(False)
+        elif name == "rowsum":
+            st.pop()
+            st.append(False)
+        elif name == "dot":
+            st.pop()
+            st.pop()
+            st.append(False)
+        elif OPS.get(name, 0) >= 32:
+            b = st.pop()
+            a = st.pop()
+            st.append(a or b)
+    return bool(st and st[-1])
+
+
+def fuse_row(expr, X, sides=(), agg="col_t", out=None, stream=None):
+    """C: fuse_row.  X: cuda float64 (m, n) tensor or a Csr of device tensors."""
+    lib = L.load()
+    e, keep = _expr(expr)
+    sides = list(sides)
+    if isinstance(X, Csr):
+        xs = _csr(X)
+        m, n = xs.rows, xs.cols
+        sa, ns = _sides(sides, m, n)
+        cnt = _agg_count(agg, m, n, _row_result_is_vector(expr, sides), nnz=xs.nnz)
+        out = _out(out, cnt, X.vals)
+        _check(lib.fuse_row(ctypes.byref(e), None, ctypes.byref(xs), sa, ns, AGG[agg], out.data_ptr(),
+                            _stream(stream)))
+    else:
+        xd = _dense(X)
+        sa, ns = _sides(sides, xd.rows, xd.cols)
+        cnt = _agg_count(agg, xd.rows, xd.cols, _row_result_is_vector(expr, sides))
+        out = _out(out, cnt, X)
+        _check(lib.fuse_row(ctypes.byref(e), ctypes.byref(xd), None, sa, ns, AGG[agg], out.data_ptr(),
+                            _stream(stream)))
+    return out
+
+
+def fuse_outer(expr, X, U, V, sides=(), agg="full", out=None, stream=None):
+    """C: fuse_outer.  X: Csr of device tensors; U (m, r), V (n, r) cuda float64."""
+    lib = L.load()
+    e, keep = _expr(expr)
+    xs = _csr(X)
+    ud, vd = _dense(U), _dense(V)
+    sa, ns = _sides(list(sides), xs.rows, xs.cols)
+    out = _out(out, 1 if agg == "full" else xs.nnz, X.vals)
+    _check(lib.fuse_outer(ctypes.byref(e), ctypes.byref(xs), ctypes.byref(ud), ctypes.byref(vd), sa, ns,
+                          AGG[agg], out.data_ptr(), _stream(stream)))
+    return out
+
+
+# ----------------------------------------------------- compile-only (no device needed) ---
+
+def prepare_cell(expr, shape, sides=(), agg="full", ld=None):
+    """C: fuse_prepare_cell.  shape = (m, n); sides = [(kind, None | float)]."""
+    lib = L.load()
+    e, keep = _expr(expr)
+    xd = L.Dense(None, shape[0], shape[1], ld or max(shape[1], 1))
+    sa, ns = _sides([(k, v) for k, v in sides], shape[0], shape[1])
+    _check(lib.fuse_prepare_cell(ctypes.byref(e), ctypes.byref(xd), sa, ns, AGG[agg]))
+
+
+def prepare_magg(exprs, shape, sides=()):
+    lib = L.load()
+    pairs = [_expr(e) for e in exprs]
+    ea = (L.Expr * len(pairs))(*[p[0] for p in pairs])
+    xd = L.Dense(None, shape[0], shape[1], max(shape[1], 1))
+    sa, ns = _sides([(k, v) for k, v in sides], shape[0], shape[1])
+    _check(lib.fuse_prepare_magg(ea, len(pairs), ctypes.byref(xd), sa, ns))
+
+
+def prepare_row(expr, shape, sides=(), agg="col_t", nnz=None, rowptr64=False):
+    """C: fuse_prepare_row.  nnz=None: dense main input; else CSR with that many stored cells."""
+    lib = L.load()
+    e, keep = _expr(expr)
+    sa, ns = _sides([(k, v) for k, v in sides], shape[0], shape[1])
+    if nnz is None:
+        xd = L.Dense(None, shape[0], shape[1], max(shape[1], 1))
+        _check(lib.fuse_prepare_row(ctypes.byref(e), ctypes.byref(xd), None, sa, ns, AGG[agg]))
+    else:
+        xs = L.CsrDesc(None, None, None, int(rowptr64), shape[0], shape[1], int(nnz))
+        _check(lib.fuse_prepare_row(ctypes.byref(e), None, ctypes.byref(xs), sa, ns, AGG[agg]))
+
+
+def prepare_outer(expr, shape, rank, nnz, sides=(), agg="full", rowptr64=False):
+    lib = L.load()
+    e, keep = _expr(expr)
+    xs = L.CsrDesc(None, None, None, int(rowptr64), shape[0], shape[1], int(nnz))
+    ud = L.Dense(None, shape[0], rank, rank)
+    vd = L.Dense(None, shape[1], rank, rank)
+    sa, ns = _sides([(k, v) for k, v in sides], shape[0], shape[1])
+    _check(lib.fuse_prepare_outer(ctypes.byref(e), ctypes.byref(xs), ctypes.byref(ud), ctypes.byref(vd), sa, ns,
+                                  AGG[agg]))
+
+
+# ------------------------------------------------------------------------- utilities ---
+
+def cache_stats():
+    """(hits, misses, compile_ms) of the plan cache."""
+    h, m, ms = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_double()
+    L.load().fuse_cache_stats(ctypes.byref(h), ctypes.byref(m), ctypes.byref(ms))
+    return h.value, m.value, ms.value
+
+
+def cache_clear():
+    L.load().fuse_cache_clear()
+
+
+def last_source():
+    lib = L.load()
+    n = lib.fuse_last_source(None, 0)
+    buf = ctypes.create_string_buffer(n + 1)
+    lib.fuse_last_source(buf, n + 1)
+    return buf.value.decode()
+
+
+def last_kernel():
+    return L.load().fuse_last_kernel().decode()
+
+
+def probe_copy(dst, src, blocks, stream=None):
+    _check(L.load().fuse_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel(), int(blocks), _stream(stream)))
+
+
+def probe_read(src, sink, blocks, stream=None):
+    _check(L.load().fuse_probe_read(src.data_ptr(), src.numel(), int(blocks), sink.data_ptr(), _stream(stream)))

@@ -1,0 +1,26 @@
+/* Kernel argument block shared by the host launcher and the hipRTC-compiled
+ * skeletons (this file's text is prepended to every generated source). */
+#ifndef FUSE_ARGS_H
+#define FUSE_ARGS_H
+
+#define FUSE_MAX_SIDES 8
+#define FUSE_MAX_AGGS 16
+
+typedef struct {
+    const double *x;                          /* dense main input, or CSR values      */
+    const int *colidx;                        /* CSR column indices                   */
+    const void *rowptr;                       /* CSR row offsets (int32 or int64)     */
+    const double *side[FUSE_MAX_SIDES];       /* side inputs (device)                 */
+    long long side_ld[FUSE_MAX_SIDES];        /* leading dimension / row stride       */
+    double side_scalar[FUSE_MAX_SIDES];       /* scalar sides                         */
+    const double *u, *v;                      /* Outer factors                        */
+    long long ldu, ldv;
+    long long m, n, ld, nnz;                  /* shape of the main input              */
+    double *out;
+    double *partials;                         /* workspace: per-block partial sums    */
+    unsigned int *ticket;                     /* workspace: zeroed arrival counter    */
+    int rank;                                 /* Outer: columns of U and V            */
+    int pad_;
+} fuse_kargs;
+
+#endif

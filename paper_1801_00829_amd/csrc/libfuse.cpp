@@ -1,0 +1,764 @@
+// libfuse C ABI: validation, kernel selection and launch for the four template
+// entry points (see include/fuse.h for the contract of every call).
+#include "../../include/fuse.h"
+
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+#include <string>
+
+#include "expr.h"
+#include "runtime.h"
+
+namespace {
+
+using namespace fuse;
+
+// ---- skeleton sources, embedded as text --------------------------------------
+const char *kSrcArgs =
+#include "gen_args_text.inc"
+    ;
+const char *kSrcCommon =
+#include "skel_common.inc"
+    ;
+const char *kSrcCell =
+#include "skel_cell.inc"
+    ;
+const char *kSrcRowDense =
+#include "skel_row_dense.inc"
+    ;
+const char *kSrcRowCsr =
+#include "skel_row_csr.inc"
+    ;
+const char *kSrcOuter =
+#include "skel_outer.inc"
+    ;
+
+thread_local std::string g_err;
+thread_local std::string g_last_source;
+thread_local std::string g_last_kernel;
+
+int fail(int code, const std::string &msg)
+{
+    g_err = msg;
+    return code;
+}
+
+int env_int(const char *name, int dflt)
+{
+    const char *e = std::getenv(name);
+    return (e && *e) ? std::atoi(e) : dflt;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int next_pow2(int64_t v)
+{
+    int p = 1;
+    while (p < v)
+        p <<= 1;
+    return p;
+}
+
+struct SideInfo {
+    int kind[FUSE_MAX_SIDES];
+};
+
+// Shape checks shared by all templates: side k against an m x n main input.
+int check_sides(const fuse_side *sides, int nsides, int64_t m, int64_t n, bool need_data,
+                const bool *used)
+{
+    if (nsides < 0 || nsides > FUSE_MAX_SIDES)
+        return fail(FUSE_EINVAL, "nsides must be in [0, " + std::to_string(FUSE_MAX_SIDES) + "]");
+    if (nsides > 0 && !sides)
+        return fail(FUSE_EINVAL, "sides is NULL");
+    for (int k = 0; k < nsides; ++k) {
+        const fuse_side &s = sides[k];
+        const std::string at = "side " + std::to_string(k) + ": ";
+        switch (s.kind) {
+        case FUSE_SIDE_MATRIX:
+            if (s.m.rows != m || s.m.cols != n)
+                return fail(FUSE_ESHAPE, at + "matrix side must be " + std::to_string(m) + " x " + std::to_string(n));
+            if (s.m.ld < n)
+                return fail(FUSE_ESHAPE, at + "ld < cols");
+            break;
+        case FUSE_SIDE_COLVEC:
+            if (s.m.rows != m || s.m.cols != 1)
+                return fail(FUSE_ESHAPE, at + "column-vector side must be " + std::to_string(m) + " x 1");
+            if (s.m.ld < 1)
+                return fail(FUSE_ESHAPE, at + "ld < 1");
+            break;
+        case FUSE_SIDE_ROWVEC:
+            if (s.m.rows != 1 || s.m.cols != n)
+                return fail(FUSE_ESHAPE, at + "row-vector side must be 1 x " + std::to_string(n));
+            break;
+        case FUSE_SIDE_SCALAR:
+            break;
+        default:
+            return fail(FUSE_EINVAL, at + "unknown side kind " + std::to_string(s.kind));
+        }
+        if (need_data && used[k] && s.kind != FUSE_SIDE_SCALAR && !s.m.data && m * n > 0)
+            return fail(FUSE_EINVAL, at + "data is NULL");
+    }
+    return 0;
+}
+
+int check_dense(const fuse_dense *X, const char *what, bool need_data)
+{
+    if (!X)
+        return fail(FUSE_EINVAL, std::string(what) + " is NULL");
+    if (X->rows < 0 || X->cols < 0)
+        return fail(FUSE_EINVAL, std::string(what) + ": negative shape");
+    if (X->ld < X->cols)
+        return fail(FUSE_ESHAPE, std::string(what) + ": ld < cols");
+    if (need_data && !X->data && X->rows * X->cols > 0)
+        return fail(FUSE_EINVAL, std::string(what) + ": data is NULL");
+    return 0;
+}
+
+int check_csr(const fuse_csr *X, bool need_data)
+{
+    if (!X)
+        return fail(FUSE_EINVAL, "X is NULL");
+    if (X->rows < 0 || X->cols < 0 || X->nnz < 0)
+        return fail(FUSE_EINVAL, "X: negative shape or nnz");
+    if (X->cols > 2147483647LL)
+        return fail(FUSE_EUNSUPPORTED, "X: more than 2^31-1 columns (int32 column indices)");
+    if (!X->rowptr_is64 && X->nnz > 2147483647LL)
+        return fail(FUSE_EINVAL, "X: nnz does not fit the int32 row offsets");
+    if (X->nnz > X->rows * X->cols && X->rows * X->cols >= 0 && X->cols > 0 && X->rows <= (int64_t)4e18 / X->cols)
+        return fail(FUSE_ESHAPE, "X: nnz exceeds rows * cols");
+    if (need_data && (!X->rowptr || (X->nnz > 0 && (!X->vals || !X->colidx))))
+        return fail(FUSE_EINVAL, "X: NULL CSR array");
+    return 0;
+}
+
+std::string side_tables(const fuse_side *sides, int nsides, const bool *used)
+{
+    std::string s = "#define FUSE_NSIDES " + std::to_string(nsides) + "\n";
+    s += "static __device__ constexpr int fuse_side_kind[] = {";
+    for (int k = 0; k < nsides; ++k)
+        s += std::to_string(sides[k].kind) + ", ";
+    s += "-1};\nstatic __device__ constexpr bool fuse_side_used[] = {";
+    for (int k = 0; k < nsides; ++k)
+        s += std::string(used[k] ? "true" : "false") + ", ";
+    s += "false};\n";
+    return s;
+}
+
+std::string side_key(const fuse_side *sides, int nsides)
+{
+    std::string s = "sides:";
+    for (int k = 0; k < nsides; ++k)
+        s += std::to_string(sides[k].kind);
+    return s;
+}
+
+void fill_side_args(fuse_kargs &A, const fuse_side *sides, int nsides)
+{
+    for (int k = 0; k < nsides; ++k) {
+        A.side[k] = sides[k].m.data;
+        A.side_ld[k] = sides[k].kind == FUSE_SIDE_ROWVEC ? 0 : sides[k].m.ld;
+        A.side_scalar[k] = sides[k].scalar;
+    }
+}
+
+int zero_fill(Plan::Loaded &fn, double *out, int64_t count, hipStream_t stream)
+{
+    if (count <= 0)
+        return 0;
+    struct {
+        double *out;
+        long long n;
+        double v;
+    } a = {out, count, 0.0};
+    unsigned gx = (unsigned)std::min<int64_t>((count + 255) / 256, 1024);
+    return Runtime::get().launch(fn.fill, gx, 1, 256, stream, &a, sizeof a, g_err);
+}
+
+int run_combine(Plan::Loaded &fn, const double *partials, int nblocks, int nv, double *out,
+                hipStream_t stream)
+{
+    struct {
+        const double *partials;
+        int nblocks, nv;
+        double *out;
+    } a = {partials, nblocks, nv, out};
+    return Runtime::get().launch(fn.combine, (unsigned)((nv + 3) / 4), 1, 256, stream, &a, sizeof a, g_err);
+}
+
+int agg_code(int agg)
+{
+    switch (agg) {
+    case FUSE_AGG_NONE: return 0;
+    case FUSE_AGG_FULL: return 1;
+    case FUSE_AGG_ROW: return 2;
+    case FUSE_AGG_COL:
+    case FUSE_AGG_COL_T: return 3;
+    }
+    return -1;
+}
+
+// ------------------------------------------------------------------ row (dense) --
+// Shared by fuse_row (dense) and by Cell bodies that need the 2-D form.
+int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dense *X,
+                   const fuse_side *sides, int nsides, int agg, double *out, hipStream_t stream,
+                   bool launch, const char *name_prefix)
+{
+    Runtime &rt = Runtime::get();
+    const int64_t m = X->rows, n = X->cols;
+    const int ac = agg_code(agg);
+    if (prog.result_vec ? false : (ac == 2 || ac == 3))
+        return fail(FUSE_EDESC, "row / column aggregation needs a row-vector result");
+
+    // vector width: 16-byte loads need even strides and aligned bases
+    bool vec2 = (n % 2 == 0) && (X->ld % 2 == 0) && (!launch || aligned16(X->data));
+    for (int k = 0; k < nsides && vec2; ++k) {
+        if (!prog.side_used[k])
+            continue;
+        if (sides[k].kind == FUSE_SIDE_MATRIX)
+            vec2 = (sides[k].m.ld % 2 == 0) && (!launch || aligned16(sides[k].m.data));
+        else if (sides[k].kind == FUSE_SIDE_ROWVEC)
+            vec2 = !launch || aligned16(sides[k].m.data);
+    }
+    if (ac == 0 && prog.result_vec && launch && !aligned16(out))
+        vec2 = false;
+    const int VEC = vec2 ? 2 : 1;
+    const int64_t nvec = (n + VEC - 1) / VEC;
+    // lanes per row and vectors per lane
+    const int epl_target = env_int("FUSE_ROW_EPL", 8);
+    int G = 1;
+    while (G < 64 && (nvec + G - 1) / G > epl_target)
+        G <<= 1;
+    int64_t epl64 = (nvec + G - 1) / G;
+    int stripes = 1;
+    if (epl64 > 16) {
+        if (prog.nstage > 0)
+            return fail(FUSE_EUNSUPPORTED, "Row bodies with ROWSUM / DOT need cols <= " +
+                                               std::to_string(64 * 16 * VEC) + " for dense input");
+        epl64 = 16;
+        stripes = (int)((n + (int64_t)64 * 16 * VEC - 1) / ((int64_t)64 * 16 * VEC));
+    }
+    if (epl64 < 1)
+        epl64 = 1;
+    const int EPL = (int)epl64;
+    int RS = env_int("FUSE_ROW_RS", 0);
+    if (RS <= 0)
+        RS = EPL >= 8 ? 1 : (EPL >= 4 ? 2 : 4);
+    const int BLOCK = 256;
+
+    const std::string key = std::string("rowdense|") + pkey + "|" + side_key(sides, nsides) + "|agg" +
+                            std::to_string(ac) + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
+                            std::to_string(EPL) + "r" + std::to_string(RS) + "nt" +
+                            std::to_string(env_int("FUSE_NT", 0));
+    std::shared_ptr<Plan> plan;
+    int rc = rt.plan(key, name_prefix, [&](const std::string &name) {
+        std::string s = kSrcArgs;
+        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 0)) + "\n";
+        s += kSrcCommon;
+        s += "#define FUSE_KERNEL_NAME " + name + "\n";
+        s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_EPL " + std::to_string(EPL) +
+             "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_RS " + std::to_string(RS) +
+             "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_AGG " + std::to_string(ac) + "\n";
+        s += side_tables(sides, nsides, prog.side_used);
+        s += emit_row_body(prog);
+        s += kSrcRowDense;
+        g_last_source = s;
+        return s;
+    }, plan, g_err);
+    if (rc)
+        return rc;
+    g_last_kernel = plan->kernel_name;
+    if (!launch)
+        return 0;
+
+    Plan::Loaded fn;
+    if ((rc = rt.load(*plan, fn, g_err)))
+        return rc;
+    const int64_t out_count = ac == 0 ? (prog.result_vec ? m * n : m) : ac == 1 ? 1 : ac == 2 ? m : n;
+    if (m == 0 || n == 0)
+        return zero_fill(fn, out, out_count, stream);
+
+    const int NW = BLOCK / 64;
+    const int64_t rows_per_iter = (int64_t)(64 / G) * RS * NW;
+    const int cus = rt.num_cus();
+    int64_t gx = (m + rows_per_iter - 1) / rows_per_iter;
+    const int64_t cap = std::max<int64_t>(1, (int64_t)cus * env_int("FUSE_ROW_BLOCKS_PER_CU", 4) / stripes);
+    gx = std::min(gx, cap);
+    Workspace ws;
+    size_t need = 64;
+    if (ac == 3)
+        need = (size_t)gx * (size_t)n;
+    else if (ac == 1)
+        need = (size_t)gx * stripes;
+    else if (ac == 2 && stripes > 1)
+        need = (size_t)stripes * (size_t)m;
+    if ((rc = rt.workspace(stream, need, ws, g_err)))
+        return rc;
+
+    fuse_kargs A;
+    std::memset(&A, 0, sizeof A);
+    A.x = X->data;
+    A.m = m;
+    A.n = n;
+    A.ld = X->ld;
+    A.out = out;
+    A.partials = ws.partials;
+    A.ticket = ws.ticket;
+    fill_side_args(A, sides, nsides);
+    if ((rc = rt.launch(fn.main, (unsigned)gx, (unsigned)stripes, BLOCK, stream, &A, sizeof A, g_err)))
+        return rc;
+    if (ac == 3)
+        return run_combine(fn, ws.partials, (int)gx, (int)n, out, stream);
+    if (ac == 2 && stripes > 1)
+        return run_combine(fn, ws.partials, stripes, (int)m, out, stream);
+    return 0;
+}
+
+// ------------------------------------------------------------------ cell / magg --
+int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides, int nsides,
+              int agg, double *out, void *stream_, bool launch, bool is_magg)
+{
+    g_err.clear();
+    Runtime &rt = Runtime::get();
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!exprs)
+        return fail(FUSE_EINVAL, "expr is NULL");
+    if (k < 1 || k > FUSE_MAX_AGGS)
+        return fail(FUSE_EINVAL, "k must be in [1, " + std::to_string(FUSE_MAX_AGGS) + "]");
+    int rc = check_dense(X, "X", launch);
+    if (rc)
+        return rc;
+    const int ac = agg_code(agg);
+    if (ac < 0)
+        return fail(FUSE_EINVAL, "unknown aggregation " + std::to_string(agg));
+    if (launch && !out)
+        return fail(FUSE_EINVAL, "out is NULL");
+    const int64_t m = X->rows, n = X->cols;
+    Program prog;
+    {
+        // shape checks need to know which sides are used; parse first with kinds only
+        if (nsides < 0 || nsides > FUSE_MAX_SIDES || (nsides > 0 && !sides))
+            return fail(FUSE_EINVAL, "bad sides / nsides");
+        for (int q = 0; q < nsides; ++q)
+            if (sides[q].kind < 0 || sides[q].kind > 3)
+                return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
+        rc = parse_program(Tmpl::CELL, exprs, k, sides, nsides, prog, g_err);
+        if (rc)
+            return rc;
+    }
+    if ((rc = check_sides(sides, nsides, m, n, launch, prog.side_used)))
+        return rc;
+
+    // flat form: one contiguous index space
+    bool flat = (ac == 0 || ac == 1) && (X->ld == n || m <= 1);
+    for (int q = 0; q < nsides && flat; ++q)
+        if (prog.side_used[q]) {
+            if (sides[q].kind == FUSE_SIDE_MATRIX)
+                flat = sides[q].m.ld == n || m <= 1;
+            else if (sides[q].kind != FUSE_SIDE_SCALAR)
+                flat = false;
+        }
+    if (!flat) {
+        if (is_magg)
+            return fail(FUSE_EUNSUPPORTED, "MAgg needs contiguous matrices (ld == cols) and only matrix / "
+                                           "scalar side inputs in this build");
+        Program rprog;
+        if ((rc = parse_program(Tmpl::ROW_DENSE, exprs, 1, sides, nsides, rprog, g_err)))
+            return rc;
+        return row_dense_impl(rprog, program_key(rprog), X, sides, nsides, agg, out, stream, launch,
+                              "fuse_cell2d");
+    }
+
+    bool vec2 = !launch || aligned16(X->data);
+    for (int q = 0; q < nsides && vec2; ++q)
+        if (prog.side_used[q] && sides[q].kind == FUSE_SIDE_MATRIX)
+            vec2 = !launch || aligned16(sides[q].m.data);
+    if (ac == 0 && launch && !aligned16(out))
+        vec2 = false;
+    const int VEC = vec2 ? 2 : 1;
+    int nmat = 1;
+    for (int q = 0; q < nsides; ++q)
+        nmat += prog.side_used[q] && sides[q].kind == FUSE_SIDE_MATRIX;
+    int UNROLL = env_int("FUSE_CELL_UNROLL", 0);
+    if (UNROLL <= 0)
+        UNROLL = nmat <= 2 ? 8 : (nmat <= 4 ? 4 : 2);
+
+    const std::string key = std::string(is_magg ? "magg|" : "cell|") + program_key(prog) + "|" +
+                            side_key(sides, nsides) + "|agg" + std::to_string(ac) + "|v" + std::to_string(VEC) +
+                            "u" + std::to_string(UNROLL) + "nt" + std::to_string(env_int("FUSE_NT", 0));
+    std::shared_ptr<Plan> plan;
+    rc = rt.plan(key, is_magg ? "fuse_magg" : "fuse_cell", [&](const std::string &name) {
+        std::string s = kSrcArgs;
+        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 0)) + "\n";
+        s += kSrcCommon;
+        s += "#define FUSE_KERNEL_NAME " + name + "\n";
+        s += "#define FUSE_K " + std::to_string(k) + "\n#define FUSE_VEC " + std::to_string(VEC) +
+             "\n#define FUSE_UNROLL " + std::to_string(UNROLL) + "\n#define FUSE_FULL " + std::to_string(ac == 1) + "\n";
+        s += side_tables(sides, nsides, prog.side_used);
+        s += "#define FUSE_SIDE_IS_MATRIX(k) (fuse_side_kind[k] == 0 && fuse_side_used[k])\n";
+        s += emit_cell_body(prog);
+        s += kSrcCell;
+        g_last_source = s;
+        return s;
+    }, plan, g_err);
+    if (rc)
+        return rc;
+    g_last_kernel = plan->kernel_name;
+    if (!launch)
+        return 0;
+
+    Plan::Loaded fn;
+    if ((rc = rt.load(*plan, fn, g_err)))
+        return rc;
+    const int64_t N = m * n;
+    if (N == 0)
+        return zero_fill(fn, out, ac == 1 ? k : 0, stream);
+    const int64_t nvec = N / VEC;
+    const int cus = rt.num_cus();
+    int64_t gx = (nvec + (int64_t)256 * UNROLL - 1) / ((int64_t)256 * UNROLL);
+    gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CELL_BLOCKS_PER_CU", 8)));
+    Workspace ws;
+    if ((rc = rt.workspace(stream, (size_t)gx * k, ws, g_err)))
+        return rc;
+    fuse_kargs A;
+    std::memset(&A, 0, sizeof A);
+    A.x = X->data;
+    A.m = m;
+    A.n = n;
+    A.ld = n;
+    A.out = out;
+    A.partials = ws.partials;
+    A.ticket = ws.ticket;
+    fill_side_args(A, sides, nsides);
+    return rt.launch(fn.main, (unsigned)gx, 1, 256, stream, &A, sizeof A, g_err);
+}
+
+// ------------------------------------------------------------------------- row --
+int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides, int nsides, int agg,
+                 double *out, hipStream_t stream, bool launch)
+{
+    Runtime &rt = Runtime::get();
+    const int64_t m = X->rows, n = X->cols;
+    const int ac = agg_code(agg);
+    if (!prog.result_vec && (ac == 2 || ac == 3))
+        return fail(FUSE_EDESC, "row / column aggregation needs a row-vector result");
+
+    // lanes per row from the mean row length
+    int G = env_int("FUSE_CSR_G", 0);
+    if (G <= 0) {
+        const double avg = m > 0 ? (double)X->nnz / (double)m : 1.0;
+        G = std::min(64, std::max(4, next_pow2((int64_t)(avg * 1.3 + 0.999))));
+    }
+    const int RS = std::max(1, env_int("FUSE_CSR_RS", 2));
+    const int BLOCK = std::max(64, env_int("FUSE_CSR_BLOCK", 512));
+
+    // LDS plan: the column accumulator first, then staged row-vector sides if they fit
+    int nrv = 0;
+    for (int k = 0; k < nsides; ++k)
+        nrv += prog.side_used[k] && sides[k].kind == FUSE_SIDE_ROWVEC;
+    const int64_t lds_budget = 64000;
+    if (ac == 3 && n * 8 > lds_budget - 4096)
+        return fail(FUSE_EUNSUPPORTED, "CSR Row with column aggregation needs cols <= " +
+                                           std::to_string((lds_budget - 4096) / 8));
+    const bool stage_rv = nrv > 0 && ((ac == 3 ? n : 0) + (int64_t)nrv * n) * 8 <= lds_budget - 1024;
+    const int64_t npad = (ac == 3 || stage_rv) ? std::max<int64_t>(n, 1) : 1;
+
+    const std::string key = std::string("rowcsr|") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
+                            std::to_string(ac) + "|g" + std::to_string(G) + "r" + std::to_string(RS) + "b" +
+                            std::to_string(BLOCK) + "p" + std::to_string(npad) + "s" + std::to_string(stage_rv) +
+                            "w" + std::to_string(X->rowptr_is64 != 0) + "nt" + std::to_string(env_int("FUSE_NT", 0));
+    std::shared_ptr<Plan> plan;
+    int rc = rt.plan(key, "fuse_row_csr", [&](const std::string &name) {
+        std::string s = kSrcArgs;
+        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 0)) + "\n";
+        s += kSrcCommon;
+        s += "#define FUSE_KERNEL_NAME " + name + "\n";
+        s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_RS " + std::to_string(RS) +
+             "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_AGG " + std::to_string(ac) +
+             "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) + "\n#define FUSE_NPAD " +
+             std::to_string(npad) + "\n#define FUSE_STAGE_RV " + std::to_string(stage_rv) +
+             "\n#define FUSE_NRV " + std::to_string(std::max(nrv, 1)) + "\n";
+        s += side_tables(sides, nsides, prog.side_used);
+        s += emit_row_body(prog);
+        s += kSrcRowCsr;
+        g_last_source = s;
+        return s;
+    }, plan, g_err);
+    if (rc)
+        return rc;
+    g_last_kernel = plan->kernel_name;
+    if (!launch)
+        return 0;
+
+    Plan::Loaded fn;
+    if ((rc = rt.load(*plan, fn, g_err)))
+        return rc;
+    const int64_t out_count = ac == 0 ? (prog.result_vec ? X->nnz : m) : ac == 1 ? 1 : ac == 2 ? m : n;
+    if (m == 0)
+        return zero_fill(fn, out, out_count, stream);
+
+    const int cus = rt.num_cus();
+    const int NW = BLOCK / 64;
+    const int64_t rows_per_iter = (int64_t)(64 / G) * RS * NW;
+    int64_t gx = (m + rows_per_iter - 1) / rows_per_iter;
+    gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CSR_BLOCKS_PER_CU", 2)));
+    Workspace ws;
+    const size_t need = ac == 3 ? (size_t)gx * (size_t)n : (size_t)gx;
+    if ((rc = rt.workspace(stream, need, ws, g_err)))
+        return rc;
+    fuse_kargs A;
+    std::memset(&A, 0, sizeof A);
+    A.x = X->vals;
+    A.colidx = X->colidx;
+    A.rowptr = X->rowptr;
+    A.m = m;
+    A.n = n;
+    A.nnz = X->nnz;
+    A.out = out;
+    A.partials = ws.partials;
+    A.ticket = ws.ticket;
+    fill_side_args(A, sides, nsides);
+    if ((rc = rt.launch(fn.main, (unsigned)gx, 1, BLOCK, stream, &A, sizeof A, g_err)))
+        return rc;
+    if (ac == 3)
+        return run_combine(fn, ws.partials, (int)gx, (int)n, out, stream);
+    return 0;
+}
+
+int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, const fuse_side *sides,
+             int nsides, int agg, double *out, void *stream_, bool launch)
+{
+    g_err.clear();
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!expr)
+        return fail(FUSE_EINVAL, "expr is NULL");
+    if ((Xd != nullptr) == (Xs != nullptr))
+        return fail(FUSE_EINVAL, "exactly one of Xd / Xs must be given");
+    if (agg_code(agg) < 0)
+        return fail(FUSE_EINVAL, "unknown aggregation " + std::to_string(agg));
+    if (launch && !out)
+        return fail(FUSE_EINVAL, "out is NULL");
+    int rc = Xd ? check_dense(Xd, "Xd", launch) : check_csr(Xs, launch);
+    if (rc)
+        return rc;
+    if (nsides < 0 || nsides > FUSE_MAX_SIDES || (nsides > 0 && !sides))
+        return fail(FUSE_EINVAL, "bad sides / nsides");
+    for (int q = 0; q < nsides; ++q)
+        if (sides[q].kind < 0 || sides[q].kind > 3)
+            return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
+    Program prog;
+    if ((rc = parse_program(Xd ? Tmpl::ROW_DENSE : Tmpl::ROW_CSR, expr, 1, sides, nsides, prog, g_err)))
+        return rc;
+    const int64_t m = Xd ? Xd->rows : Xs->rows, n = Xd ? Xd->cols : Xs->cols;
+    if ((rc = check_sides(sides, nsides, m, n, launch, prog.side_used)))
+        return rc;
+    if (Xd)
+        return row_dense_impl(prog, program_key(prog), Xd, sides, nsides, agg, out, stream, launch,
+                              "fuse_row_dense");
+    return row_csr_impl(prog, Xs, sides, nsides, agg, out, stream, launch);
+}
+
+// ----------------------------------------------------------------------- outer --
+int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
+               const fuse_side *sides, int nsides, int agg, double *out, void *stream_, bool launch)
+{
+    g_err.clear();
+    Runtime &rt = Runtime::get();
+    hipStream_t stream = (hipStream_t)stream_;
+    if (!expr)
+        return fail(FUSE_EINVAL, "expr is NULL");
+    int rc = check_csr(X, launch);
+    if (rc)
+        return rc;
+    if ((rc = check_dense(U, "U", launch)) || (rc = check_dense(V, "V", launch)))
+        return rc;
+    if (agg != FUSE_AGG_FULL && agg != FUSE_AGG_NONE)
+        return fail(agg_code(agg) < 0 ? FUSE_EINVAL : FUSE_EUNSUPPORTED,
+                    "Outer supports FUSE_AGG_FULL and FUSE_AGG_NONE in this build");
+    if (launch && !out)
+        return fail(FUSE_EINVAL, "out is NULL");
+    if (U->rows != X->rows || V->rows != X->cols || U->cols != V->cols)
+        return fail(FUSE_ESHAPE, "Outer needs U: rows(X) x r and V: cols(X) x r");
+    const int64_t r = U->cols;
+    if (r < 1 || r > 1024)
+        return fail(FUSE_EUNSUPPORTED, "Outer rank must be in [1, 1024]");
+    if (nsides < 0 || nsides > FUSE_MAX_SIDES || (nsides > 0 && !sides))
+        return fail(FUSE_EINVAL, "bad sides / nsides");
+    for (int q = 0; q < nsides; ++q)
+        if (sides[q].kind < 0 || sides[q].kind > 3)
+            return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
+    Program prog;
+    if ((rc = parse_program(Tmpl::OUTER, expr, 1, sides, nsides, prog, g_err)))
+        return rc;
+    if ((rc = check_sides(sides, nsides, X->rows, X->cols, launch, prog.side_used)))
+        return rc;
+
+    const bool vec2 = (r % 2 == 0) && (U->ld % 2 == 0) && (V->ld % 2 == 0) &&
+                      (!launch || (aligned16(U->data) && aligned16(V->data)));
+    const int VEC = vec2 ? 2 : 1;
+    const int64_t nvec = (r + VEC - 1) / VEC;
+    // lanes per inner product: least padding with at most 8 vectors per lane
+    int G = env_int("FUSE_OUTER_G", 0);
+    if (G <= 0) {
+        double best = 1e30;
+        for (int g = 1; g <= 64; g <<= 1) {
+            const int64_t epl = (nvec + g - 1) / g;
+            if (epl > 8)
+                continue;
+            const double waste = (double)(epl * g) / (double)nvec + 0.02 * g / 64.0 * 0;
+            if (waste < best - 1e-12) {
+                best = waste;
+                G = g;
+            }
+        }
+        if (G <= 0)
+            G = 64;
+    }
+    const int EPL = (int)((nvec + G - 1) / G);
+    int UNR = env_int("FUSE_OUTER_UNR", 0);
+    if (UNR <= 0)
+        UNR = EPL >= 7 ? 2 : (EPL >= 3 ? 4 : 8);
+    UNR = std::min(UNR, G);
+    while (G % UNR)
+        --UNR;
+    const int BLOCK = std::max(64, env_int("FUSE_OUTER_BLOCK", 256));
+    bool need_col = false;
+    for (int q = 0; q < nsides; ++q)
+        need_col |= prog.side_used[q] && (sides[q].kind == FUSE_SIDE_MATRIX || sides[q].kind == FUSE_SIDE_ROWVEC);
+
+    const std::string key = std::string("outer|") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
+                            std::to_string(agg) + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
+                            std::to_string(EPL) + "u" + std::to_string(UNR) + "b" + std::to_string(BLOCK) + "w" +
+                            std::to_string(X->rowptr_is64 != 0);
+    std::shared_ptr<Plan> plan;
+    rc = rt.plan(key, "fuse_outer", [&](const std::string &name) {
+        std::string s = kSrcArgs;
+        s += "#define FUSE_NT 0\n";
+        s += kSrcCommon;
+        s += "#define FUSE_KERNEL_NAME " + name + "\n";
+        s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_EPL " + std::to_string(EPL) +
+             "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_UNR " + std::to_string(UNR) +
+             "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_FULL " +
+             std::to_string(agg == FUSE_AGG_FULL) + "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) +
+             "\n#define FUSE_NEED_COL " + std::to_string(need_col) + "\n";
+        s += side_tables(sides, nsides, prog.side_used);
+        s += emit_outer_body(prog);
+        s += kSrcOuter;
+        g_last_source = s;
+        return s;
+    }, plan, g_err);
+    if (rc)
+        return rc;
+    g_last_kernel = plan->kernel_name;
+    if (!launch)
+        return 0;
+
+    Plan::Loaded fn;
+    if ((rc = rt.load(*plan, fn, g_err)))
+        return rc;
+    if (X->rows == 0 || X->nnz == 0)
+        return zero_fill(fn, out, agg == FUSE_AGG_FULL ? 1 : 0, stream);
+    const int cus = rt.num_cus();
+    const int NW = BLOCK / 64;
+    int64_t gx = (X->rows + NW - 1) / NW;
+    gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_OUTER_BLOCKS_PER_CU", 8)));
+    Workspace ws;
+    if ((rc = rt.workspace(stream, (size_t)gx, ws, g_err)))
+        return rc;
+    fuse_kargs A;
+    std::memset(&A, 0, sizeof A);
+    A.x = X->vals;
+    A.colidx = X->colidx;
+    A.rowptr = X->rowptr;
+    A.m = X->rows;
+    A.n = X->cols;
+    A.nnz = X->nnz;
+    A.u = U->data;
+    A.v = V->data;
+    A.ldu = U->ld;
+    A.ldv = V->ld;
+    A.rank = (int)r;
+    A.out = out;
+    A.partials = ws.partials;
+    A.ticket = ws.ticket;
+    fill_side_args(A, sides, nsides);
+    return rt.launch(fn.main, (unsigned)gx, 1, BLOCK, stream, &A, sizeof A, g_err);
+}
+
+}  // namespace
+
+// =============================================================================
+extern "C" {
+
+int fuse_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_side *sides, int nsides, int agg,
+              double *out, void *stream)
+{
+    return cell_impl(expr, 1, X, sides, nsides, agg, out, stream, true, false);
+}
+
+int fuse_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides, int nsides,
+              double *out_k, void *stream)
+{
+    return cell_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, out_k, stream, true, true);
+}
+
+int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, const fuse_side *sides,
+             int nsides, int agg, double *out, void *stream)
+{
+    return row_impl(expr, Xd, Xs, sides, nsides, agg, out, stream, true);
+}
+
+int fuse_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
+               const fuse_side *sides, int nsides, int agg, double *out, void *stream)
+{
+    return outer_impl(expr, X, U, V, sides, nsides, agg, out, stream, true);
+}
+
+int fuse_prepare_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_side *sides, int nsides, int agg)
+{
+    return cell_impl(expr, 1, X, sides, nsides, agg, nullptr, nullptr, false, false);
+}
+
+int fuse_prepare_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides, int nsides)
+{
+    return cell_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, nullptr, nullptr, false, true);
+}
+
+int fuse_prepare_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, const fuse_side *sides,
+                     int nsides, int agg)
+{
+    return row_impl(expr, Xd, Xs, sides, nsides, agg, nullptr, nullptr, false);
+}
+
+int fuse_prepare_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
+                       const fuse_side *sides, int nsides, int agg)
+{
+    return outer_impl(expr, X, U, V, sides, nsides, agg, nullptr, nullptr, false);
+}
+
+const char *fuse_last_error(void) { return g_err.c_str(); }
+
+int fuse_cache_stats(int64_t *hits, int64_t *misses, double *compile_ms)
+{
+    fuse::Runtime::get().stats(hits, misses, compile_ms);
+    return FUSE_OK;
+}
+
+void fuse_cache_clear(void) { fuse::Runtime::get().clear(); }
+
+size_t fuse_last_source(char *buf, size_t buflen)
+{
+    if (buf && buflen) {
+        const size_t n = std::min(buflen - 1, g_last_source.size());
+        std::memcpy(buf, g_last_source.data(), n);
+        buf[n] = '\0';
+    }
+    return g_last_source.size();
+}
+
+const char *fuse_last_kernel(void) { return g_last_kernel.c_str(); }
+
+}  // extern "C"

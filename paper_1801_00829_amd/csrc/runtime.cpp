@@ -1,0 +1,225 @@
+#include "runtime.h"
+
+#include <hip/hiprtc.h>
+
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
+#include "../../include/fuse.h"
+
+namespace fuse {
+
+Runtime &Runtime::get()
+{
+    static Runtime *r = new Runtime();   // never destroyed: HIP may be gone at exit
+    return *r;
+}
+
+std::string Runtime::hash_hex(const std::string &s)
+{
+    uint64_t h = 1469598103934665603ull;   // FNV-1a
+    for (unsigned char c : s) {
+        h ^= c;
+        h *= 1099511628211ull;
+    }
+    char buf[20];
+    std::snprintf(buf, sizeof buf, "%016llx", (unsigned long long)h);
+    return buf;
+}
+
+std::string Runtime::arch()
+{
+    std::lock_guard<std::mutex> lk(mu_);
+    if (!arch_.empty())
+        return arch_;
+    if (const char *e = std::getenv("FUSE_ARCH")) {
+        arch_ = e;
+        return arch_;
+    }
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            prop.gcnArchName[0])
+            arch_ = prop.gcnArchName;
+    } else {
+        (void)hipGetLastError();
+    }
+    if (arch_.empty())
+        arch_ = "gfx950";
+    return arch_;
+}
+
+int Runtime::compile(Plan &p, std::string &err)
+{
+    const auto t0 = std::chrono::steady_clock::now();
+    const std::string arch_opt = "--offload-arch=" + arch();
+    hiprtcProgram prog;
+    hiprtcResult r = hiprtcCreateProgram(&prog, p.source.c_str(), (p.kernel_name + ".hip").c_str(), 0,
+                                         nullptr, nullptr);
+    if (r != HIPRTC_SUCCESS) {
+        err = std::string("hiprtcCreateProgram: ") + hiprtcGetErrorString(r);
+        return FUSE_ECOMPILE;
+    }
+    const char *opts[] = {arch_opt.c_str(), "-O3", "-std=c++17", "-Xclang", "-target-feature",
+                          "-Xclang", "-packed-fp32-ops", "-munsafe-fp-atomics"};
+    r = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
+    if (r != HIPRTC_SUCCESS) {
+        size_t n = 0;
+        hiprtcGetProgramLogSize(prog, &n);
+        std::string log(n, '\0');
+        if (n)
+            hiprtcGetProgramLog(prog, &log[0]);
+        err = std::string("hipRTC: ") + hiprtcGetErrorString(r) + "\n" + log;
+        hiprtcDestroyProgram(&prog);
+        return FUSE_ECOMPILE;
+    }
+    size_t n = 0;
+    hiprtcGetCodeSize(prog, &n);
+    p.code.resize(n);
+    hiprtcGetCode(prog, p.code.data());
+    hiprtcDestroyProgram(&prog);
+    const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    std::lock_guard<std::mutex> lk(mu_);
+    compile_ms_ += ms;
+    return 0;
+}
+
+int Runtime::load(Plan &p, Plan::Loaded &fn, std::string &err)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        err = std::string("hipGetDevice: ") + hipGetErrorString(e);
+        return FUSE_ERUNTIME;
+    }
+    std::lock_guard<std::mutex> lk(p.mu);
+    auto it = p.per_device.find(dev);
+    if (it != p.per_device.end()) {
+        fn = it->second;
+        return 0;
+    }
+    Plan::Loaded l;
+    e = hipModuleLoadData(&l.module, p.code.data());
+    if (e != hipSuccess) {
+        err = std::string("hipModuleLoadData: ") + hipGetErrorString(e);
+        return FUSE_ERUNTIME;
+    }
+    e = hipModuleGetFunction(&l.main, l.module, p.kernel_name.c_str());
+    if (e == hipSuccess)
+        e = hipModuleGetFunction(&l.combine, l.module, "fuse_combine_cols");
+    if (e == hipSuccess)
+        e = hipModuleGetFunction(&l.fill, l.module, "fuse_fill");
+    if (e != hipSuccess) {
+        err = std::string("hipModuleGetFunction: ") + hipGetErrorString(e);
+        (void)hipModuleUnload(l.module);
+        return FUSE_ERUNTIME;
+    }
+    p.per_device[dev] = l;
+    fn = l;
+    return 0;
+}
+
+int Runtime::workspace(hipStream_t stream, size_t doubles, Workspace &ws, std::string &err)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        err = std::string("hipGetDevice: ") + hipGetErrorString(e);
+        return FUSE_ERUNTIME;
+    }
+    std::lock_guard<std::mutex> lk(mu_);
+    Workspace &w = ws_[std::make_pair(dev, stream)];
+    if (!w.ticket) {
+        e = hipMalloc((void **)&w.ticket, 256);
+        if (e == hipSuccess)
+            e = hipMemset(w.ticket, 0, 256);
+        if (e != hipSuccess) {
+            w.ticket = nullptr;
+            err = std::string("workspace ticket: ") + hipGetErrorString(e);
+            return FUSE_ENOMEM;
+        }
+    }
+    if (w.partial_doubles < doubles) {
+        size_t want = doubles < 65536 ? 65536 : doubles + doubles / 4;
+        double *np = nullptr;
+        e = hipMalloc((void **)&np, want * sizeof(double));
+        if (e != hipSuccess) {
+            err = std::string("workspace partials: ") + hipGetErrorString(e);
+            return FUSE_ENOMEM;
+        }
+        if (w.partials)
+            retired_.push_back(w.partials);   // may still be read by work in flight
+        w.partials = np;
+        w.partial_doubles = want;
+    }
+    ws = w;
+    return 0;
+}
+
+int Runtime::launch(hipFunction_t f, unsigned gx, unsigned gy, unsigned block, hipStream_t stream,
+                    const void *args, size_t arg_bytes, std::string &err)
+{
+    void *config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, const_cast<void *>(args),
+                      HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_bytes, HIP_LAUNCH_PARAM_END};
+    hipError_t e = hipModuleLaunchKernel(f, gx, gy, 1, block, 1, 1, 0, stream, nullptr, config);
+    if (e != hipSuccess) {
+        err = std::string("hipModuleLaunchKernel: ") + hipGetErrorString(e);
+        return FUSE_ERUNTIME;
+    }
+    return 0;
+}
+
+int Runtime::num_cus()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess)
+        return 256;
+    std::lock_guard<std::mutex> lk(mu_);
+    auto it = cus_.find(dev);
+    if (it != cus_.end())
+        return it->second;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        n = 256;
+    cus_[dev] = n;
+    return n;
+}
+
+void Runtime::stats(int64_t *hits, int64_t *misses, double *ms)
+{
+    std::lock_guard<std::mutex> lk(mu_);
+    if (hits)
+        *hits = hits_;
+    if (misses)
+        *misses = misses_;
+    if (ms)
+        *ms = compile_ms_;
+}
+
+void Runtime::clear()
+{
+    std::lock_guard<std::mutex> lk(mu_);
+    for (auto &kv : plans_)
+        for (auto &d : kv.second->per_device)
+            if (d.second.module)
+                (void)hipModuleUnload(d.second.module);
+    plans_.clear();
+    for (auto &kv : ws_) {
+        if (kv.second.partials)
+            (void)hipFree(kv.second.partials);
+        if (kv.second.ticket)
+            (void)hipFree(kv.second.ticket);
+    }
+    ws_.clear();
+    for (void *p : retired_)
+        (void)hipFree(p);
+    retired_.clear();
+    hits_ = misses_ = 0;
+    compile_ms_ = 0.0;
+}
+
+}  // namespace fuse

@@ -1,0 +1,98 @@
+// hipRTC compilation, plan cache, per-stream workspaces and kernel launch.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "fuse_args.h"
+
+namespace fuse {
+
+// One compiled body + skeleton (a "generated operator class" of Sec. 2.1).
+struct Plan {
+    std::string kernel_name;
+    std::string source;
+    std::vector<char> code;                 // gfx950 code object from hipRTC
+    std::mutex mu;
+    struct Loaded {
+        hipModule_t module = nullptr;
+        hipFunction_t main = nullptr;
+        hipFunction_t combine = nullptr;    // fuse_combine_cols
+        hipFunction_t fill = nullptr;       // fuse_fill
+    };
+    std::map<int, Loaded> per_device;
+};
+
+struct Workspace {
+    double *partials = nullptr;
+    size_t partial_doubles = 0;
+    unsigned int *ticket = nullptr;
+};
+
+class Runtime {
+public:
+    static Runtime &get();
+
+    // Look up `key`; on a miss build the source with `make_source(kernel_name)`
+    // and compile it.  Returns FUSE_OK / FUSE_ECOMPILE (message in err).
+    template <typename F>
+    int plan(const std::string &key, const std::string &name_prefix, F make_source,
+             std::shared_ptr<Plan> &out, std::string &err)
+    {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            auto it = plans_.find(key);
+            if (it != plans_.end()) {
+                ++hits_;
+                out = it->second;
+                return 0;
+            }
+        }
+        const std::string name = name_prefix + "_" + hash_hex(key);
+        auto p = std::make_shared<Plan>();
+        p->kernel_name = name;
+        p->source = make_source(name);
+        int rc = compile(*p, err);
+        if (rc != 0)
+            return rc;
+        std::lock_guard<std::mutex> lk(mu_);
+        ++misses_;
+        auto ins = plans_.emplace(key, p);
+        out = ins.first->second;
+        return 0;
+    }
+
+    // Load (once per device) and return the functions of a plan on the current device.
+    int load(Plan &p, Plan::Loaded &fn, std::string &err);
+    // Workspace of (current device, stream) with room for `doubles` partials.
+    int workspace(hipStream_t stream, size_t doubles, Workspace &ws, std::string &err);
+    int launch(hipFunction_t f, unsigned gx, unsigned gy, unsigned block, hipStream_t stream,
+               const void *args, size_t arg_bytes, std::string &err);
+
+    int num_cus();
+    void stats(int64_t *hits, int64_t *misses, double *ms);
+    void clear();
+
+    static std::string hash_hex(const std::string &s);
+
+private:
+    int compile(Plan &p, std::string &err);
+    std::string arch();
+
+    std::mutex mu_;
+    std::unordered_map<std::string, std::shared_ptr<Plan>> plans_;
+    std::map<std::pair<int, hipStream_t>, Workspace> ws_;
+    std::vector<void *> retired_;
+    std::map<int, int> cus_;
+    std::string arch_;
+    int64_t hits_ = 0, misses_ = 0;
+    double compile_ms_ = 0.0;
+};
+
+}  // namespace fuse

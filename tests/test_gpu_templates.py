@@ -1,0 +1,365 @@
+"""GPU parity of the template skeletons on random expressions, all aggregation
+variants, odd shapes and edge cases, against the oracle's operator-at-a-time
+evaluation.  Integer / index work (positions of outputs on a CSR pattern,
+per-row counts, total nnz) must be bit-exact."""
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import ops, unfused
+from exprgen import random_scalar_expr, random_row_expr
+from gpu_util import to_dev, dev_sides, dev_csr, host, assert_close
+
+pytestmark = pytest.mark.gpu
+
+KINDS = ["matrix", "colvec", "rowvec", "scalar"]
+
+
+def _sides(rng, m, n, lo=-1.5, hi=1.5):
+    return [("matrix", rng.uniform(lo, hi, size=(m, n))), ("colvec", rng.uniform(lo, hi, size=m)),
+            ("rowvec", rng.uniform(lo, hi, size=n)), ("scalar", np.array(rng.uniform(lo, hi)))]
+
+
+def _abs_scale(vals_none, agg, m, n):
+    """Aggregate of |summands| in the shape of the result: the natural error scale of a sum."""
+    a = np.abs(np.nan_to_num(np.asarray(vals_none, dtype=np.float64), nan=0.0, posinf=0.0, neginf=0.0))
+    if agg == "none":
+        return None
+    a = a.reshape(m, -1)
+    if agg == "full":
+        return max(a.sum(), 1e-300)
+    if agg == "row":
+        return max(a.sum(1).max(), 1e-300)
+    return max(a.sum(0).max(), 1e-300)
+
+
+# ------------------------------------------------------------------------- Cell ---
+
+CELL_SHAPES = [(1, 1), (3, 5), (37, 129), (64, 256), (257, 100), (5, 4099), (1000, 3)]
+
+
+@pytest.mark.parametrize("case", range(14))
+def test_cell_random_expressions_all_variants(case):
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(5000 + case)
+    m, n = CELL_SHAPES[case % len(CELL_SHAPES)]
+    x = rng.uniform(-1.5, 1.5, size=(m, n))
+    x[rng.random((m, n)) < 0.1] = 0.0
+    sides = _sides(rng, m, n)
+    expr = random_scalar_expr(rng, len(KINDS))
+    xd, sd = to_dev(x), dev_sides(sides)
+    none_ref = unfused.cell(expr, x, sides, "none")
+    for agg in ("none", "full", "row", "col"):
+        print("cell case", case, (m, n), agg, expr, flush=True)
+        got = host(F.fuse_cell(expr, xd, sd, agg))
+        ref = unfused.cell(expr, x, sides, agg)
+        assert_close(got, ref, scale=_abs_scale(none_ref, agg, m, n), what="cell %s" % agg)
+
+
+def test_cell_flat_paths_and_alignment():
+    """Contiguous matrix-only bodies take the flat kernel: odd sizes, unaligned bases, no-agg store."""
+    import torch
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(7)
+    expr = [("main",), ("side", 0), ("mul",), ("side", 1), ("add",), ("abs",), ("sqrt",)]
+    for (m, n) in [(1, 1), (1, 7), (33, 31), (128, 1024), (999, 1001)]:
+        x, y, z = rng.uniform(-1, 1, size=(3, m, n))
+        ref_none = np.sqrt(np.abs(x * y + z))
+        for off in (0, 1):          # off = 1: base pointers 8-byte but not 16-byte aligned
+            def dev(a):
+                buf = torch.empty(a.size + 1, dtype=torch.float64, device="cuda")
+                v = buf[off:off + a.size].view(a.shape)
+                v.copy_(torch.from_numpy(a))
+                return v
+            xd, yd, zd = dev(x), dev(y), dev(z)
+            print("cell flat", (m, n), "offset", off, flush=True)
+            got = host(F.fuse_cell(expr, xd, [("matrix", yd), ("matrix", zd)], "full"))
+            assert_close(got, [ops.sum_full(ref_none)], what="flat full")
+            got = host(F.fuse_cell(expr, xd, [("matrix", yd), ("matrix", zd)], "none"))
+            assert_close(got, ref_none, tol=1e-15, what="flat none")
+
+
+def test_cell_strided_views():
+    """ld > cols for the main input and a matrix side; a strided column-vector side."""
+    import torch
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(8)
+    m, n = 50, 70
+    xb, yb = rng.uniform(-1, 1, size=(2, m, n + 10))
+    cb = rng.uniform(-1, 1, size=(m, 3))
+    x, y, c = xb[:, 3:3 + n], yb[:, :n], cb[:, 1]
+    expr = [("main",), ("side", 0), ("mul",), ("side", 1), ("sub",)]
+    xd, yd, cd = to_dev(xb)[:, 3:3 + n], to_dev(yb)[:, :n], to_dev(cb)[:, 1:2]
+    for agg in ("none", "full", "row", "col"):
+        got = host(F.fuse_cell(expr, xd, [("matrix", yd), ("colvec", cd)], agg))
+        ref = unfused.cell(expr, x, [("matrix", y), ("colvec", c)], agg)
+        assert_close(got, ref, scale=_abs_scale(x * y - c[:, None], agg, m, n), what="strided %s" % agg)
+
+
+def test_cell_empty_inputs():
+    import torch
+    import paper_1801_00829_amd as F
+    expr = [("main",), ("pow2",)]
+    for shape in [(0, 5), (4, 0)]:
+        x = torch.empty(shape, dtype=torch.float64, device="cuda")
+        assert host(F.fuse_cell(expr, x, [], "full")).tolist() == [0.0]
+        assert host(F.fuse_cell(expr, x, [], "row")).tolist() == [0.0] * shape[0]
+        assert host(F.fuse_cell(expr, x, [], "col")).tolist() == [0.0] * shape[1]
+        assert host(F.fuse_cell(expr, x, [], "none")).size == 0
+
+
+def test_cell_closed_forms_on_gpu():
+    import torch
+    import paper_1801_00829_amd as F
+    m, n = 777, 333
+    expr = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+    x = torch.full((m, n), 0.5, dtype=torch.float64, device="cuda")
+    assert host(F.fuse_cell(expr, x, [("matrix", x), ("matrix", x)], "full"))[0] == m * n * 0.125
+    ones = torch.ones((m, n), dtype=torch.float64, device="cuda")
+    yi = torch.arange(m, dtype=torch.float64, device="cuda")[:, None].expand(m, n).contiguous()
+    zj = torch.arange(n, dtype=torch.float64, device="cuda")[None, :].expand(m, n).contiguous()
+    assert host(F.fuse_cell(expr, ones, [("matrix", yi), ("matrix", zj)], "full"))[0] == \
+        (m * (m - 1) // 2) * (n * (n - 1) // 2)
+
+
+# ------------------------------------------------------------------------- MAgg ---
+
+@pytest.mark.parametrize("case", range(6))
+def test_magg_random_and_equals_separate_cells(case):
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(6000 + case)
+    m, n = [(1, 1), (19, 23), (300, 129), (64, 1024), (1001, 77), (2, 100001)][case]
+    k = int(rng.integers(1, 6))
+    x = rng.uniform(-1.5, 1.5, size=(m, n))
+    sides = [("matrix", rng.uniform(-1.5, 1.5, size=(m, n))), ("matrix", rng.uniform(-1.5, 1.5, size=(m, n))),
+             ("scalar", np.array(0.7))]
+    exprs = [random_scalar_expr(rng, 3, depth=3) for _ in range(k)]
+    print("magg case", case, (m, n), exprs, flush=True)
+    xd, sd = to_dev(x), dev_sides(sides)
+    got = host(F.fuse_magg(exprs, xd, sd))
+    ref = unfused.magg(exprs, x, sides)
+    for j in range(k):
+        scale = _abs_scale(unfused.cell(exprs[j], x, sides, "none"), "full", m, n)
+        assert_close(got[j], ref[j], scale=scale, what="magg[%d]" % j)
+        # a multi-aggregate equals its aggregates computed one by one
+        one = host(F.fuse_cell(exprs[j], xd, sd, "full"))
+        assert_close(got[j], one[0], scale=scale, tol=1e-13, what="magg vs cell [%d]" % j)
+
+
+# -------------------------------------------------------------------- Row dense ---
+
+ROW_SHAPES = [(1, 1), (5, 3), (70, 10), (33, 100), (129, 101), (40, 784), (17, 1000), (9, 2048), (300, 64)]
+
+
+@pytest.mark.parametrize("case", range(18))
+def test_row_dense_random_expressions(case):
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(7000 + case)
+    m, n = ROW_SHAPES[case % len(ROW_SHAPES)]
+    x = rng.uniform(-1.5, 1.5, size=(m, n))
+    sides = _sides(rng, m, n)
+    want = "V" if case % 3 else "S"
+    expr = random_row_expr(rng, KINDS, depth=3, want=want)
+    xd, sd = to_dev(x), dev_sides(sides)
+    none_ref = unfused.row_dense(expr, x, sides, "none")
+    for agg in (("none", "row", "col", "col_t", "full") if want == "V" else ("none", "full")):
+        print("row dense case", case, (m, n), agg, expr, flush=True)
+        got = host(F.fuse_row(expr, xd, sd, agg))
+        ref = unfused.row_dense(expr, x, sides, agg)
+        scale = _abs_scale(none_ref, agg, m, n if want == "V" else 1)
+        # per-row reductions feed later element-wise maths: allow for their conditioning
+        assert_close(got, ref, scale=scale, tol=1e-9, what="row dense %s" % agg)
+
+
+def test_row_dense_closed_forms_and_odd_layouts():
+    import torch
+    import paper_1801_00829_amd as F
+    expr = [("main",), ("side", 0), ("dot",), ("side", 1), ("mul",), ("main",), ("mul",)]
+    for (m, n) in [(64, 10), (1000, 100), (777, 101), (50, 1000)]:
+        x = torch.ones((m, n), dtype=torch.float64, device="cuda")
+        v = torch.ones(n, dtype=torch.float64, device="cuda")
+        w = torch.ones(m, dtype=torch.float64, device="cuda")
+        assert host(F.fuse_row(expr, x, [("rowvec", v), ("colvec", w)], "col_t")).tolist() == [float(m * n)] * n
+    # ld > cols and an unaligned row-vector
+    rng = np.random.default_rng(9)
+    m, n = 333, 100
+    xb = rng.normal(size=(m, n + 6))
+    vb, w = rng.normal(size=n + 1), rng.uniform(size=m)
+    x, v = xb[:, 2:2 + n], vb[1:]
+    got = host(F.fuse_row(expr, to_dev(xb)[:, 2:2 + n], [("rowvec", to_dev(vb)[1:]), ("colvec", to_dev(w))], "col_t"))
+    from oracle import plans
+    assert_close(got, plans.row_tx_w_xv(x, v, w), what="row strided")
+
+
+def test_row_dense_empty_and_limits():
+    import torch
+    import paper_1801_00829_amd as F
+    expr = [("main",), ("side", 0), ("dot",), ("main",), ("mul",)]
+    x = torch.empty((0, 8), dtype=torch.float64, device="cuda")
+    v = torch.ones(8, dtype=torch.float64, device="cuda")
+    assert host(F.fuse_row(expr, x, [("rowvec", v)], "col_t")).tolist() == [0.0] * 8
+    big = torch.ones((2, 4098), dtype=torch.float64, device="cuda")
+    with pytest.raises(F.FuseError) as e:
+        F.fuse_row(expr, big, [("rowvec", torch.ones(4098, dtype=torch.float64, device="cuda"))], "col_t")
+    assert e.value.code == -7
+
+
+# ---------------------------------------------------------------------- Row CSR ---
+
+def _csr_cases():
+    yield "bernoulli", W.csr_bernoulli(500, 300, 0.03, 101), (500, 300)
+    yield "fixed10", W.csr_fixed_per_row(257, 1000, 10, 102), (257, 1000)
+    yield "skewed", W.csr_skewed(400, 900, 0.01, 4, 0.7, 103), (400, 900)
+    yield "dense", W.csr_bernoulli(40, 70, 1.0, 104), (40, 70)
+    yield "one_row", W.csr_bernoulli(1, 5000, 0.3, 105), (1, 5000)
+    yield "one_col", W.csr_bernoulli(3000, 1, 0.5, 106), (3000, 1)
+    rp = np.zeros(301, dtype=np.int64)
+    yield "all_empty", (rp, np.zeros(0, np.int32), np.zeros(0)), (300, 50)
+    rp, ci, va = W.csr_bernoulli(200, 64, 0.2, 107)
+    keep = np.repeat(np.arange(200) % 3 != 0, np.diff(rp))       # empty every third row
+    counts = np.where(np.arange(200) % 3 != 0, np.diff(rp), 0)
+    rp2 = np.zeros(201, np.int64)
+    np.cumsum(counts, out=rp2[1:])
+    yield "many_empty_rows", (rp2, ci[keep], va[keep]), (200, 64)
+
+
+@pytest.mark.parametrize("rowptr64", [False, True])
+def test_row_csr_workload_expression_on_all_patterns(rowptr64):
+    import paper_1801_00829_amd as F
+    from oracle import plans
+    expr = [("main",), ("side", 0), ("dot",), ("main",), ("mul",)]
+    for name, (rp, ci, va), shape in _csr_cases():
+        print("row csr pattern", name, shape, "rowptr64" if rowptr64 else "rowptr32", flush=True)
+        v = np.random.default_rng(3).normal(size=shape[1])
+        got = host(F.fuse_row(expr, dev_csr(rp, ci, va, shape, rowptr64), [("rowvec", to_dev(v))], "col_t"))
+        x = ops.make_csr(rp, ci, va, shape)
+        ref = plans.row_csr_tx_xv(x, v)
+        q = ops.csr_matvec(x, np.abs(v))
+        scale = max(np.abs(ops.csr_t_matvec(x, q)).max(), 1e-300) if va.size else 1.0
+        assert_close(got, ref, scale=scale, what="row csr " + name)
+
+
+def test_row_csr_index_handling_is_bit_exact():
+    """Counts and positions: with X = 1 on its pattern, row / column / full sums of
+    the body `X` are integer counts; the no-agg output must sit at the exact positions."""
+    import paper_1801_00829_amd as F
+    for name, (rp, ci, va), shape in _csr_cases():
+        print("row csr exact", name, flush=True)
+        m, n = shape
+        xd = dev_csr(rp, ci, np.ones_like(va), shape)
+        body = [("main",)]
+        assert np.array_equal(host(F.fuse_row(body, xd, [], "row")), np.diff(rp).astype(np.float64))
+        assert np.array_equal(host(F.fuse_row(body, xd, [], "col")), np.bincount(ci, minlength=n).astype(np.float64))
+        assert host(F.fuse_row(body, xd, [], "full"))[0] == float(rp[-1])
+        # positions: out[p] = X_p * colvec[row(p)] * rowvec[col(p)] with integer-valued sides
+        rows = np.repeat(np.arange(m), np.diff(rp))
+        cv, rv = np.arange(m, dtype=np.float64) + 1, np.arange(n, dtype=np.float64) + 1
+        e2 = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+        got = host(F.fuse_row(e2, xd, [("colvec", to_dev(cv)), ("rowvec", to_dev(rv))], "none"))
+        assert np.array_equal(got, cv[rows] * rv[ci])
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_row_csr_random_sparse_safe_expressions(case):
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(8000 + case)
+    m, n = [(1, 1), (37, 19), (300, 257), (64, 1000), (513, 40), (100, 3000)][case % 6]
+    rp, ci, va = W.csr_bernoulli(m, n, [0.5, 0.2, 0.04, 0.01, 0.3, 0.005][case % 6], 8000 + case)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    sides = _sides(rng, m, n)
+    want = "V" if case % 3 else "S"
+    expr = random_row_expr(rng, KINDS, depth=3, want=want, sparse_safe=True)
+    xd, sd = dev_csr(rp, ci, va, (m, n)), dev_sides(sides)
+    none_ref = unfused.row_csr(expr, x, sides, "none")
+    for agg in (("none", "row", "col", "col_t", "full") if want == "V" else ("none", "full")):
+        print("row csr case", case, (m, n), agg, expr, flush=True)
+        got = host(F.fuse_row(expr, xd, sd, agg))
+        ref = unfused.row_csr(expr, x, sides, agg)
+        if want == "V" and agg != "none":
+            a = np.abs(np.nan_to_num(none_ref, nan=0.0, posinf=0.0, neginf=0.0))
+            scale = {"full": a.sum(), "row": ops.csr_row_sums(x, a).max(initial=0.0),
+                     "col": ops.csr_col_sums(x, a).max(initial=0.0)}[agg.replace("col_t", "col")]
+        elif want == "S" and agg == "full":
+            scale = np.abs(np.nan_to_num(none_ref, nan=0.0, posinf=0.0, neginf=0.0)).sum()
+        else:
+            scale = None
+        assert_close(got, ref, scale=None if scale is None else max(scale, 1e-300), tol=1e-9,
+                     what="row csr %s" % agg)
+
+
+def test_row_csr_rejects_programs_that_are_not_sparse_safe():
+    import paper_1801_00829_amd as F
+    rp, ci, va = W.csr_bernoulli(10, 10, 0.3, 1)
+    xd = dev_csr(rp, ci, va, (10, 10))
+    with pytest.raises(F.FuseError) as e:
+        F.fuse_row([("main",), ("const", 1.0), ("add",)], xd, [], "col")
+    assert e.value.code == -3
+
+
+# ------------------------------------------------------------------------ Outer ---
+
+@pytest.mark.parametrize("case", range(12))
+def test_outer_random_expressions(case):
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(9000 + case)
+    m, n, r = [(1, 1, 1), (30, 20, 7), (200, 300, 100), (64, 64, 20), (500, 100, 33), (40, 2000, 128)][case % 6]
+    dens = [1.0, 0.3, 0.02, 0.1, 0.05, 0.01][case % 6]
+    rp, ci, va = W.csr_bernoulli(m, n, dens, 9000 + case)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    u, v = rng.uniform(size=(m, r)), rng.uniform(size=(n, r))
+    sides = _sides(rng, m, n)
+    expr = random_scalar_expr(rng, len(KINDS), extra_leaf="uvdot") if case >= 2 else \
+        [("main",), ("uvdot",), ("const", 1e-15), ("add",), ("log",), ("mul",)]
+    xd, ud, vd, sd = dev_csr(rp, ci, va, (m, n)), to_dev(u), to_dev(v), dev_sides(sides)
+    none_ref = unfused.outer(expr, x, u, v, sides, "none")
+    for agg in ("none", "full"):
+        print("outer case", case, (m, n, r), agg, expr, flush=True)
+        got = host(F.fuse_outer(expr, xd, ud, vd, sd, agg))
+        ref = unfused.outer(expr, x, u, v, sides, agg)
+        scale = None if agg == "none" else max(np.abs(np.nan_to_num(none_ref, nan=0, posinf=0, neginf=0)).sum(), 1e-300)
+        assert_close(got, ref, scale=scale, tol=1e-9 if agg == "full" else 1e-10, what="outer %s" % agg)
+
+
+def test_outer_closed_forms_patterns_and_index_exactness():
+    import math
+    import paper_1801_00829_amd as F
+    body = [("main",), ("uvdot",), ("const", 1e-15), ("add",), ("log",), ("mul",)]
+    for name, (rp, ci, va), shape in _csr_cases():
+        m, n = shape
+        for r in (100, 7):
+            print("outer pattern", name, shape, "rank", r, flush=True)
+            xd = dev_csr(rp, ci, np.ones_like(va), shape)
+            u, v = np.ones((m, r)), np.ones((n, r))
+            got = host(F.fuse_outer(body, xd, to_dev(u), to_dev(v), [], "full"))[0]
+            assert abs(got - va.size * math.log(r + 1e-15)) <= 1e-12 * max(1.0, va.size * math.log(r + 1e-15))
+            # exact index handling: uvdot alone with U_i = (i+1) e_0, V_j = (j+1) e_0 gives (i+1)(j+1) at p
+            u2, v2 = np.zeros((m, r)), np.zeros((n, r))
+            u2[:, 0], v2[:, 0] = np.arange(m) + 1, np.arange(n) + 1
+            got = host(F.fuse_outer([("uvdot",)], xd, to_dev(u2), to_dev(v2), [], "none"))
+            rows = np.repeat(np.arange(m), np.diff(rp))
+            assert np.array_equal(got, (rows + 1.0) * (ci + 1.0))
+            # number of processed stored cells == rowptr[m]
+            assert host(F.fuse_outer([("main",), ("neq0",)], xd, to_dev(u2), to_dev(v2), [], "full"))[0] == float(rp[-1])
+    # zero rows of U: every stored cell of those rows contributes x * log(1e-15)
+    rp, ci, va = W.csr_bernoulli(60, 50, 0.2, 11)
+    u = np.ones((60, 100))
+    u[::2] = 0.0
+    x = ops.make_csr(rp, ci, va, (60, 50))
+    from oracle import plans
+    got = host(F.fuse_outer(body, dev_csr(rp, ci, va, (60, 50)), to_dev(u), to_dev(np.ones((50, 100))), [], "full"))
+    assert_close(got, plans.outer_sum_x_log_uv(x, u, np.ones((50, 100))), what="outer zero rows")
+
+
+def test_outer_rowptr64_and_strided_factors():
+    import paper_1801_00829_amd as F
+    from oracle import plans
+    rng = np.random.default_rng(12)
+    m, n, r = 150, 130, 100
+    rp, ci, va = W.csr_bernoulli(m, n, 0.05, 13)
+    ub, vb = rng.uniform(size=(m, r + 4)), rng.uniform(size=(n, r + 3))
+    x = ops.make_csr(rp, ci, va, (m, n))
+    ref = plans.outer_sum_x_log_uv(x, ub[:, :r], vb[:, :r])
+    body = [("main",), ("uvdot",), ("const", 1e-15), ("add",), ("log",), ("mul",)]
+    for rp64 in (False, True):
+        got = host(F.fuse_outer(body, dev_csr(rp, ci, va, (m, n), rp64), to_dev(ub)[:, :r], to_dev(vb)[:, :r], [], "full"))
+        assert_close(got, ref, what="outer strided rp64=%s" % rp64)

@@ -1,0 +1,211 @@
+"""Host-side checks of libfuse without a GPU: exported symbols, validation and
+error codes, descriptor type checking, hipRTC compilation of generated bodies
+for gfx950 (hipRTC needs no device), plan-cache behaviour."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def F():
+    import paper_1801_00829_amd as F
+    from paper_1801_00829_amd import build as B
+    if B.needs_build():
+        B.build()
+    return F
+
+
+def test_library_exports_every_declared_symbol(F):
+    hdr = open(os.path.join(ROOT, "include", "fuse.h")).read()
+    declared = set(re.findall(r"^(?:int|void|size_t|const char \*)\s*\*?(fuse_\w+)\(", hdr, flags=re.M))
+    assert {"fuse_cell", "fuse_magg", "fuse_row", "fuse_outer", "fuse_last_error", "fuse_cache_stats",
+            "fuse_cache_clear", "fuse_prepare_cell", "fuse_prepare_magg", "fuse_prepare_row",
+            "fuse_prepare_outer", "fuse_last_source", "fuse_last_kernel", "fuse_probe_copy",
+            "fuse_probe_read"} <= declared
+    lib = ctypes.CDLL(F.lib_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_binding_opcodes_match_header(F):
+    hdr = open(os.path.join(ROOT, "include", "fuse.h")).read()
+    body = hdr[hdr.index("typedef enum {\n    /* leaves */"):hdr.index("} fuse_op;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    val, enum = -1, {}
+    for item in body.replace("typedef enum {", "").split(","):
+        item = item.strip()
+        if not item:
+            continue
+        if "=" in item:
+            name, v = [t.strip() for t in item.split("=")]
+            val = int(v)
+        else:
+            name, val = item, val + 1
+        enum[name] = val
+    for name, code in F.OPS.items():
+        assert enum["FUSE_OP_" + name.upper()] == code, name
+
+
+XYZ = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+
+
+def test_prepare_compiles_the_five_workloads_and_caches(F):
+    F.cache_clear()
+    two = [("matrix", None), ("matrix", None)]
+    F.prepare_cell(XYZ, (1000, 1000), two, "full")
+    assert F.last_kernel().startswith("fuse_cell_")
+    src = F.last_source()
+    assert "r[0] = ((a * s[0]) * s[1]);" in src and "fuse_grid_finish" in src
+    F.prepare_magg([XYZ[:3], [("main",), ("side", 1), ("mul",)], [("main",), ("pow2",)]], (100000, 1000), two)
+    assert "r[2] = fuse_pow2(a);" in F.last_source()
+    F.prepare_row([("main",), ("side", 0), ("dot",), ("side", 1), ("mul",), ("main",), ("mul",)], (1000000, 100),
+                  [("rowvec", None), ("colvec", None)], "col_t")
+    src = F.last_source()
+    assert "part[0] += (a * sv[0]);" in src and "return ((red[0] * rsc[1]) * a);" in src
+    assert "#define FUSE_G 8" in src and "#define FUSE_EPL 7" in src and "#define FUSE_VEC 2" in src
+    F.prepare_row([("main",), ("side", 0), ("dot",), ("main",), ("mul",)], (10000000, 1000), [("rowvec", None)],
+                  "col_t", nnz=100000000)
+    assert F.last_kernel().startswith("fuse_row_csr_") and "#define FUSE_G 16" in F.last_source()
+    F.prepare_outer([("main",), ("uvdot",), ("const", 1e-15), ("add",), ("log",), ("mul",)], (100000, 100000), 100,
+                    10000000)
+    assert "return (a * log((d + (0x1.203af9ee75616p-50))));" in F.last_source()
+    hits, misses, ms = F.cache_stats()
+    assert (hits, misses) == (0, 5) and ms > 0
+    # equal descriptors are compiled once (plan cache)
+    F.prepare_cell(XYZ, (1000, 1000), two, "full")
+    F.prepare_cell(XYZ, (123, 77), two, "full")          # the shape is not part of a flat Cell plan
+    assert F.cache_stats()[:2] == (2, 5)
+    F.prepare_cell(XYZ, (1000, 1000), two, "none")       # another variant is another plan
+    assert F.cache_stats()[:2] == (2, 6)
+
+
+def test_constants_round_trip_exactly(F):
+    for c in (1e-15, 0.1, -2.5e300, 5e-324):
+        F.prepare_cell([("main",), ("const", c), ("add",)], (4, 4), [], "full")
+        lit = re.search(r"r\[0\] = \(a \+ \((-?0x[0-9a-fp.+-]+)\)\);", F.last_source()).group(1)
+        assert float.fromhex(lit) == c
+
+
+@pytest.mark.parametrize("expr,code", [
+    ([("main",), ("mul",)], -3),                              # binary operator with one operand
+    ([("main",), ("main",)], -3),                             # two values left on the stack
+    ([("main",), ("side", 5), ("mul",)], -3),                 # side index out of range
+    ([("main",), ("rowsum",)], -3),                           # row token in a Cell body
+    ([("uvdot",)], -3),                                       # Outer token in a Cell body
+    ([], -1),                                                 # empty expression
+])
+def test_cell_descriptor_errors(F, expr, code):
+    with pytest.raises(F.FuseError) as e:
+        F.prepare_cell(expr, (8, 8), [("matrix", None)], "full")
+    assert e.value.code == code
+    assert str(e.value)
+
+
+def test_shape_and_argument_errors(F):
+    from paper_1801_00829_amd import _lib as L
+    lib = L.load()
+    e, keep = F.api._expr(XYZ)
+    x = L.Dense(None, 8, 8, 8)
+    sides = (L.Side * 2)()
+    sides[0].kind, sides[0].m = 0, L.Dense(None, 8, 9, 9)      # wrong shape
+    sides[1].kind, sides[1].m = 0, L.Dense(None, 8, 8, 8)
+    assert lib.fuse_prepare_cell(ctypes.byref(e), ctypes.byref(x), sides, 2, 1) == -2
+    assert b"side 0" in lib.fuse_last_error()
+    sides[0].m = L.Dense(None, 8, 8, 4)                        # ld < cols
+    assert lib.fuse_prepare_cell(ctypes.byref(e), ctypes.byref(x), sides, 2, 1) == -2
+    sides[0].m = L.Dense(None, 8, 8, 8)
+    assert lib.fuse_prepare_cell(ctypes.byref(e), ctypes.byref(x), sides, 2, 9) == -1     # bad aggregation
+    assert lib.fuse_prepare_cell(None, ctypes.byref(x), sides, 2, 1) == -1
+    assert lib.fuse_prepare_cell(ctypes.byref(e), None, sides, 2, 1) == -1
+    assert lib.fuse_prepare_cell(ctypes.byref(e), ctypes.byref(x), sides, 9, 1) == -1     # too many sides
+    assert lib.fuse_prepare_cell(ctypes.byref(e), ctypes.byref(x), sides, 2, 1) == 0
+    assert lib.fuse_last_error() == b""
+    # launching calls reject NULL data / out before touching the device
+    assert lib.fuse_cell(ctypes.byref(e), ctypes.byref(x), sides, 2, 1, None, None) == -1
+    # Row: exactly one main input
+    xs = L.CsrDesc(None, None, None, 0, 8, 8, 10)
+    assert lib.fuse_prepare_row(ctypes.byref(e), ctypes.byref(x), ctypes.byref(xs), sides, 2, 3) == -1
+    assert lib.fuse_prepare_row(ctypes.byref(e), None, None, sides, 2, 3) == -1
+    # CSR: nnz beyond int32 offsets, nnz > rows * cols
+    big = L.CsrDesc(None, None, None, 0, 1 << 20, 1 << 20, 1 << 31)
+    assert lib.fuse_prepare_row(ctypes.byref(e), None, ctypes.byref(big), sides, 0, 3) in (-1, -3)
+    assert lib.fuse_prepare_outer(ctypes.byref(e), ctypes.byref(L.CsrDesc(None, None, None, 0, 4, 4, 17)),
+                                  ctypes.byref(L.Dense(None, 4, 3, 3)), ctypes.byref(L.Dense(None, 4, 3, 3)),
+                                  None, 0, 1) == -2
+    # Outer: factor shapes
+    ok = L.CsrDesc(None, None, None, 0, 4, 6, 5)
+    e2, keep2 = F.api._expr([("main",), ("uvdot",), ("mul",)])
+    assert lib.fuse_prepare_outer(ctypes.byref(e2), ctypes.byref(ok), ctypes.byref(L.Dense(None, 4, 3, 3)),
+                                  ctypes.byref(L.Dense(None, 6, 3, 3)), None, 0, 1) == 0
+    assert lib.fuse_prepare_outer(ctypes.byref(e2), ctypes.byref(ok), ctypes.byref(L.Dense(None, 6, 3, 3)),
+                                  ctypes.byref(L.Dense(None, 4, 3, 3)), None, 0, 1) == -2
+    assert lib.fuse_prepare_outer(ctypes.byref(e2), ctypes.byref(ok), ctypes.byref(L.Dense(None, 4, 3, 3)),
+                                  ctypes.byref(L.Dense(None, 6, 3, 3)), None, 0, 2) == -7    # row agg: not built
+
+
+def test_row_type_checking_and_sparse_safety(F):
+    dot_v = [("main",), ("side", 0), ("dot",)]
+    F.prepare_row(dot_v, (100, 10), [("rowvec", None)], "none")            # scalar result, per row
+    F.prepare_row(dot_v, (100, 10), [("rowvec", None)], "full")
+    with pytest.raises(F.FuseError) as e:
+        F.prepare_row(dot_v, (100, 10), [("rowvec", None)], "col")          # column sums of a scalar
+    assert e.value.code == -3
+    with pytest.raises(F.FuseError) as e:
+        F.prepare_row([("side", 0), ("rowsum",)], (100, 10), [("colvec", None)], "none")   # rowsum of a scalar
+    assert e.value.code == -3
+    # two reduction stages: rowsum(X * rowsum(X))
+    nested = [("main",), ("main",), ("rowsum",), ("mul",), ("rowsum",)]
+    F.prepare_row(nested, (100, 10), [], "none")
+    src = F.last_source()
+    assert "#define FUSE_NSTAGE 2" in src and "part[1] += (a * red[0]);" in src
+    # CSR: sparse-safe bodies compile, others are rejected with FUSE_EDESC
+    F.prepare_row([("main",), ("side", 0), ("mul",), ("abs",)], (100, 10), [("matrix", None)], "col", nnz=50)
+    for bad in ([("main",), ("const", 1.0), ("add",)], [("main",), ("exp",)],
+                [("side", 0), ("rowsum",), ("main",), ("mul",)], [("main",), ("side", 0), ("add",), ("rowsum",)]):
+        with pytest.raises(F.FuseError) as e:
+            F.prepare_row(bad, (100, 10), [("matrix", None)], "col", nnz=50)
+        assert e.value.code == -3 and "sparse-safe" in str(e.value)
+    # dense Row limit on the width of reductions
+    with pytest.raises(F.FuseError) as e:
+        F.prepare_row(dot_v, (10, 5000), [("rowvec", None)], "none")
+    assert e.value.code == -7
+
+
+def test_every_operator_compiles(F):
+    un = ["neg", "abs", "sqrt", "exp", "log", "pow2", "sign", "neq0", "sigmoid"]
+    bi = ["add", "sub", "mul", "div", "min", "max", "pow", "lt", "le", "gt", "ge", "eq", "ne"]
+    expr = [("main",)]
+    for u in un:
+        expr += [(u,)]
+    for b in bi:
+        expr += [("side", 0), (b,)]
+    F.prepare_cell(expr, (16, 16), [("matrix", None)], "full")
+    F.prepare_cell(expr, (16, 16), [("colvec", None)], "row")              # 2-D form of the Cell skeleton
+    assert F.last_kernel().startswith("fuse_cell2d_")
+    F.prepare_outer(expr + [("uvdot",), ("mul",)], (16, 16), 5, 20, [("rowvec", None)], "none")
+
+
+def test_missing_library_fails_loudly(tmp_path, monkeypatch):
+    from paper_1801_00829_amd import _lib as L
+    monkeypatch.setattr(L, "_lib", None)
+    monkeypatch.setattr(L, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        L.load()
+
+
+def test_cost_arithmetic_matches_the_papers_worked_example():
+    """bytes / bandwidth helper of the benchmark against the example printed with the cost model."""
+    import importlib
+    bench = importlib.import_module("bench")
+    vals = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "cost_model_example.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            vals[k] = float(v)
+    nbytes = vals["rows"] * vals["cols"] * vals["bytes_per_cell"]
+    assert bench.seconds_at(nbytes, vals["bandwidth_GBps"]) == vals["seconds"]
+    assert bench.gbps(nbytes, vals["seconds"]) == vals["bandwidth_GBps"]
