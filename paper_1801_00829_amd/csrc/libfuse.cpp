@@ -334,9 +334,9 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
     const int ac = agg_code(agg);
     if (ac < 0)
         return fail(FUSE_EINVAL, "unknown aggregation " + std::to_string(agg));
-    if (launch && !out)
-        return fail(FUSE_EINVAL, "out is NULL");
     const int64_t m = X->rows, n = X->cols;
+    if (launch && !out && (ac == 1 ? k : ac == 0 ? m * n : ac == 2 ? m : n) > 0)
+        return fail(FUSE_EINVAL, "out is NULL");
     Program prog;
     {
         // shape checks need to know which sides are used; parse first with kinds only
@@ -539,8 +539,6 @@ int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, co
         return fail(FUSE_EINVAL, "exactly one of Xd / Xs must be given");
     if (agg_code(agg) < 0)
         return fail(FUSE_EINVAL, "unknown aggregation " + std::to_string(agg));
-    if (launch && !out)
-        return fail(FUSE_EINVAL, "out is NULL");
     int rc = Xd ? check_dense(Xd, "Xd", launch) : check_csr(Xs, launch);
     if (rc)
         return rc;
@@ -555,6 +553,13 @@ int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, co
     const int64_t m = Xd ? Xd->rows : Xs->rows, n = Xd ? Xd->cols : Xs->cols;
     if ((rc = check_sides(sides, nsides, m, n, launch, prog.side_used)))
         return rc;
+    {
+        const int ac = agg_code(agg);
+        const int64_t cells = Xd ? m * n : Xs->nnz;
+        const int64_t count = ac == 1 ? 1 : ac == 2 ? m : ac == 3 ? n : (prog.result_vec ? cells : m);
+        if (launch && !out && count > 0)
+            return fail(FUSE_EINVAL, "out is NULL");
+    }
     if (Xd)
         return row_dense_impl(prog, program_key(prog), Xd, sides, nsides, agg, out, stream, launch,
                               "fuse_row_dense");
@@ -578,7 +583,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     if (agg != FUSE_AGG_FULL && agg != FUSE_AGG_NONE)
         return fail(agg_code(agg) < 0 ? FUSE_EINVAL : FUSE_EUNSUPPORTED,
                     "Outer supports FUSE_AGG_FULL and FUSE_AGG_NONE in this build");
-    if (launch && !out)
+    if (launch && !out && (agg == FUSE_AGG_FULL || X->nnz > 0))
         return fail(FUSE_EINVAL, "out is NULL");
     if (U->rows != X->rows || V->rows != X->cols || U->cols != V->cols)
         return fail(FUSE_ESHAPE, "Outer needs U: rows(X) x r and V: cols(X) x r");

@@ -76,7 +76,7 @@ def test_cell_flat_paths_and_alignment():
             got = host(F.fuse_cell(expr, xd, [("matrix", yd), ("matrix", zd)], "full"))
             assert_close(got, [ops.sum_full(ref_none)], what="flat full")
             got = host(F.fuse_cell(expr, xd, [("matrix", yd), ("matrix", zd)], "none"))
-            assert_close(got, ref_none, tol=1e-15, what="flat none")
+            assert_close(got, ref_none, tol=1e-12, what="flat none")   # fused multiply-add vs two roundings
 
 
 def test_cell_strided_views():
