@@ -228,7 +228,7 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     const int VEC = vec2 ? 2 : 1;
     const int64_t nvec = (n + VEC - 1) / VEC;
     // lanes per row and vectors per lane
-    const int epl_target = env_int("FUSE_ROW_EPL", 8);
+    const int epl_target = env_int("FUSE_ROW_EPL", 4);
     int G = 1;
     while (G < 64 && (nvec + G - 1) / G > epl_target)
         G <<= 1;
@@ -246,17 +246,17 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     const int EPL = (int)epl64;
     int RS = env_int("FUSE_ROW_RS", 0);
     if (RS <= 0)
-        RS = EPL >= 8 ? 1 : (EPL >= 4 ? 2 : 4);
+        RS = EPL >= 8 ? 1 : (EPL >= 3 ? 2 : 4);
     const int BLOCK = 256;
 
     const std::string key = std::string("rowdense|") + pkey + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(ac) + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
                             std::to_string(EPL) + "r" + std::to_string(RS) + "nt" +
-                            std::to_string(env_int("FUSE_NT", 0));
+                            std::to_string(env_int("FUSE_NT", 1));
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, name_prefix, [&](const std::string &name) {
         std::string s = kSrcArgs;
-        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 0)) + "\n";
+        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 1)) + "\n";
         s += kSrcCommon;
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
         s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_EPL " + std::to_string(EPL) +
@@ -285,7 +285,7 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     const int64_t rows_per_iter = (int64_t)(64 / G) * RS * NW;
     const int cus = rt.num_cus();
     int64_t gx = (m + rows_per_iter - 1) / rows_per_iter;
-    const int64_t cap = std::max<int64_t>(1, (int64_t)cus * env_int("FUSE_ROW_BLOCKS_PER_CU", 4) / stripes);
+    const int64_t cap = std::max<int64_t>(1, (int64_t)cus * env_int("FUSE_ROW_BLOCKS_PER_CU", 2) / stripes);
     gx = std::min(gx, cap);
     Workspace ws;
     size_t need = 64;
@@ -384,15 +384,15 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
         nmat += prog.side_used[q] && sides[q].kind == FUSE_SIDE_MATRIX;
     int UNROLL = env_int("FUSE_CELL_UNROLL", 0);
     if (UNROLL <= 0)
-        UNROLL = nmat <= 2 ? 8 : (nmat <= 4 ? 4 : 2);
+        UNROLL = nmat <= 1 ? 8 : (nmat <= 2 ? 4 : 2);
 
     const std::string key = std::string(is_magg ? "magg|" : "cell|") + program_key(prog) + "|" +
                             side_key(sides, nsides) + "|agg" + std::to_string(ac) + "|v" + std::to_string(VEC) +
-                            "u" + std::to_string(UNROLL) + "nt" + std::to_string(env_int("FUSE_NT", 0));
+                            "u" + std::to_string(UNROLL) + "nt" + std::to_string(env_int("FUSE_NT", 1));
     std::shared_ptr<Plan> plan;
     rc = rt.plan(key, is_magg ? "fuse_magg" : "fuse_cell", [&](const std::string &name) {
         std::string s = kSrcArgs;
-        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 0)) + "\n";
+        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 1)) + "\n";
         s += kSrcCommon;
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
         s += "#define FUSE_K " + std::to_string(k) + "\n#define FUSE_VEC " + std::to_string(VEC) +
@@ -418,8 +418,8 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
         return zero_fill(fn, out, ac == 1 ? k : 0, stream);
     const int64_t nvec = N / VEC;
     const int cus = rt.num_cus();
-    int64_t gx = (nvec + (int64_t)256 * UNROLL - 1) / ((int64_t)256 * UNROLL);
-    gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CELL_BLOCKS_PER_CU", 8)));
+    int64_t gx = std::max<int64_t>(nvec / ((int64_t)256 * UNROLL), (N + 255) / 256 > 4 ? 4 : 1);
+    gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CELL_BLOCKS_PER_CU", 1)));
     Workspace ws;
     if ((rc = rt.workspace(stream, (size_t)gx * k, ws, g_err)))
         return rc;
@@ -447,13 +447,21 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
         return fail(FUSE_EDESC, "row / column aggregation needs a row-vector result");
 
     // lanes per row from the mean row length
+    // lanes per row (G) and register-resident cells per lane (C): C*G covers rows of
+    // about 1.6 x the mean length; short rows use few lanes so that the group
+    // butterfly is paid once per C*G cells
     int G = env_int("FUSE_CSR_G", 0);
-    if (G <= 0) {
+    int C = env_int("FUSE_CSR_C", 0);
+    if (G <= 0 || C <= 0) {
         const double avg = m > 0 ? (double)X->nnz / (double)m : 1.0;
-        G = std::min(64, std::max(4, next_pow2((int64_t)(avg * 1.3 + 0.999))));
+        const int cover = next_pow2((int64_t)(avg * 1.6 + 0.999));
+        C = cover >= 16 ? 4 : (cover >= 4 ? 2 : 1);
+        G = std::min(64, std::max(1, cover / C));
+        if (cover > 256)
+            C = 4, G = 64;
     }
-    const int RS = std::max(1, env_int("FUSE_CSR_RS", 2));
-    const int BLOCK = std::max(64, env_int("FUSE_CSR_BLOCK", 512));
+    const int RS = std::max(1, env_int("FUSE_CSR_RS", 1));
+    const int BLOCK = std::max(64, env_int("FUSE_CSR_BLOCK", 1024));
 
     // LDS plan: the column accumulator first, then staged row-vector sides if they fit
     int nrv = 0;
@@ -467,18 +475,22 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     const int64_t npad = (ac == 3 || stage_rv) ? std::max<int64_t>(n, 1) : 1;
 
     const std::string key = std::string("rowcsr|") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
-                            std::to_string(ac) + "|g" + std::to_string(G) + "r" + std::to_string(RS) + "b" +
+                            std::to_string(ac) + "|g" + std::to_string(G) + "c" + std::to_string(C) + "r" + std::to_string(RS) + "b" +
                             std::to_string(BLOCK) + "p" + std::to_string(npad) + "s" + std::to_string(stage_rv) +
-                            "w" + std::to_string(X->rowptr_is64 != 0) + "nt" + std::to_string(env_int("FUSE_NT", 0));
+                            "w" + std::to_string(X->rowptr_is64 != 0) + std::to_string(m < (1LL << 30));
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, "fuse_row_csr", [&](const std::string &name) {
         std::string s = kSrcArgs;
-        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 0)) + "\n";
+        // plain (cached) loads: the register slots of neighbouring rows overlap in
+        // memory, so lines are re-used from cache rather than streamed once
+        s += "#define FUSE_NT 0\n";
         s += kSrcCommon;
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
-        s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_RS " + std::to_string(RS) +
+        s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_C " + std::to_string(C) +
+             "\n#define FUSE_RS " + std::to_string(RS) +
              "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_AGG " + std::to_string(ac) +
-             "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) + "\n#define FUSE_NPAD " +
+             "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) + "\n#define FUSE_ROW32 " +
+             std::to_string(m < (1LL << 30)) + "\n#define FUSE_NPAD " +
              std::to_string(npad) + "\n#define FUSE_STAGE_RV " + std::to_string(stage_rv) +
              "\n#define FUSE_NRV " + std::to_string(std::max(nrv, 1)) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
@@ -504,7 +516,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     const int NW = BLOCK / 64;
     const int64_t rows_per_iter = (int64_t)(64 / G) * RS * NW;
     int64_t gx = (m + rows_per_iter - 1) / rows_per_iter;
-    gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CSR_BLOCKS_PER_CU", 2)));
+    gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CSR_BLOCKS_PER_CU", 1)));
     Workspace ws;
     const size_t need = ac == 3 ? (size_t)gx * (size_t)n : (size_t)gx;
     if ((rc = rt.workspace(stream, need, ws, g_err)))
@@ -517,6 +529,13 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     A.m = m;
     A.n = n;
     A.nnz = X->nnz;
+    if (X->nnz == 0) {
+        // no stored cell at all: the kernel's (masked) loads still need a valid
+        // address, so point them at one dummy cell inside the workspace
+        A.x = ws.partials;
+        A.colidx = reinterpret_cast<const int *>(ws.ticket) + 16;   // stays zero
+        A.nnz = 1;
+    }
     A.out = out;
     A.partials = ws.partials;
     A.ticket = ws.ticket;

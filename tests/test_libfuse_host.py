@@ -66,10 +66,10 @@ def test_prepare_compiles_the_five_workloads_and_caches(F):
                   [("rowvec", None), ("colvec", None)], "col_t")
     src = F.last_source()
     assert "part[0] += (a * sv[0]);" in src and "return ((red[0] * rsc[1]) * a);" in src
-    assert "#define FUSE_G 8" in src and "#define FUSE_EPL 7" in src and "#define FUSE_VEC 2" in src
+    assert "#define FUSE_G 16" in src and "#define FUSE_EPL 4" in src and "#define FUSE_VEC 2" in src
     F.prepare_row([("main",), ("side", 0), ("dot",), ("main",), ("mul",)], (10000000, 1000), [("rowvec", None)],
                   "col_t", nnz=100000000)
-    assert F.last_kernel().startswith("fuse_row_csr_") and "#define FUSE_G 16" in F.last_source()
+    assert F.last_kernel().startswith("fuse_row_csr_") and "#define FUSE_C " in F.last_source()
     F.prepare_outer([("main",), ("uvdot",), ("const", 1e-15), ("add",), ("log",), ("mul",)], (100000, 100000), 100,
                     10000000)
     assert "return (a * log((d + (0x1.203af9ee75616p-50))));" in F.last_source()
