@@ -384,7 +384,7 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
         nmat += prog.side_used[q] && sides[q].kind == FUSE_SIDE_MATRIX;
     int UNROLL = env_int("FUSE_CELL_UNROLL", 0);
     if (UNROLL <= 0)
-        UNROLL = nmat <= 1 ? 8 : (nmat <= 2 ? 4 : 2);
+        UNROLL = nmat <= 1 ? 8 : (nmat <= 4 ? 4 : 2);
 
     const std::string key = std::string(is_magg ? "magg|" : "cell|") + program_key(prog) + "|" +
                             side_key(sides, nsides) + "|agg" + std::to_string(ac) + "|v" + std::to_string(VEC) +
