@@ -21,6 +21,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 ALL = ("cell", "magg", "row_dense", "row_csr", "outer")
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at the full
+# workload sizes in this launch configuration, scaled by what the same counters read for
+# the 1 GiB copy probe (x2.000 for FETCH_SIZE, x1.000 for WRITE_SIZE); the summary is
+# profiles/bench_all_templates_hbm_traffic.txt.  Reported as roofline.traffic.
+MEASURED_TRAFFIC_BYTES = {"cell": 24.07e6, "magg": 2400.13e6, "row_dense": 809.00e6,
+                          "row_csr": 1372.38e6, "outer": 8739.78e6}
+
 
 def seconds_at(nbytes, gbps_):
     """Time to move nbytes at gbps_ GB/s (1 GB = 1e9 bytes)."""
@@ -31,31 +38,33 @@ def gbps(nbytes, seconds):
     return nbytes / seconds / 1e9
 
 
-def _cpu_baseline(names):
-    """The CPU oracle, as it stands, on a bounded sample (reduced row counts) of the same workloads."""
-    import workloads as W
+def _cpu_baseline(names, host):
+    """The CPU oracle, as it stands, on the host copies of the same workloads (full size)."""
     from oracle import ops, plans
-    scales = {"cell": 1.0, "magg": 0.05, "row_dense": 0.1, "row_csr": 0.02, "outer": 0.1}
-    total_bytes, total_s, parts = 0, 0.0, []
+    total_bytes, total_s, parts, results = 0, 0.0, [], {}
     for name in names:
-        w = W.make_workload(name, scales[name])
+        w = host[name]
         t0 = time.perf_counter()
         if name == "cell":
-            plans.cell_sum_xyz(w["X"], w["sides"][0][1], w["sides"][1][1])
+            r = plans.cell_sum_xyz(w["X"], w["sides"][0][1], w["sides"][1][1])
         elif name == "magg":
-            plans.magg_xy_xz_xx(w["X"], w["sides"][0][1], w["sides"][1][1])
+            r = plans.magg_xy_xz_xx(w["X"], w["sides"][0][1], w["sides"][1][1])
         elif name == "row_dense":
-            plans.row_tx_w_xv(w["X"], w["sides"][0][1], w["sides"][1][1])
+            r = plans.row_tx_w_xv(w["X"], w["sides"][0][1], w["sides"][1][1])
         elif name == "row_csr":
-            plans.row_csr_tx_xv(ops.make_csr(*w["X"]), w["sides"][0][1])
+            r = plans.row_csr_tx_xv(ops.make_csr(*w["X"]), w["sides"][0][1])
         else:
-            plans.outer_sum_x_log_uv(ops.make_csr(*w["X"]), w["U"], w["V"])
+            r = plans.outer_sum_x_log_uv(ops.make_csr(*w["X"]), w["U"], w["V"])
         dt = time.perf_counter() - t0
         total_bytes += w["bytes"]
         total_s += dt
-        parts.append("%s x%g: %.2f s" % (name, scales[name], dt))
-    return {"value": round(gbps(total_bytes, total_s), 3), "unit": "GB/s", "cores": ops.threads(),
-            "kind": "oracle", "sample": "unfused plans at reduced row counts (" + "; ".join(parts) + ")"}
+        parts.append("%s %.2f s" % (name, dt))
+        results[name] = r
+    base = {"value": round(gbps(total_bytes, total_s), 3), "unit": "GB/s", "cores": ops.threads(),
+            "kind": "oracle", "seconds": round(total_s, 3),
+            "sample": "the full workloads, one pass of the unfused operator-at-a-time plans (" +
+                      "; ".join(parts) + ")"}
+    return base, results
 
 
 def main():
@@ -65,6 +74,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--templates", default=",".join(ALL))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe", action="store_true",
+                    help="also launch the 1 GiB copy / read probes once (untimed): a transfer of known "
+                         "size that calibrates profiler byte counters collected over this command")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the fused operators are single-device kernels); "
@@ -93,7 +105,7 @@ def main():
         return F.Csr(dev(rp, torch.int32), dev(ci, torch.int32), dev(va), shape)
 
     # ---- inputs, resident in HBM before anything is timed
-    calls, info = {}, {}
+    calls, info, host, outs = {}, {}, {}, {}
     for name in names:
         t0 = time.perf_counter()
         w = W.make_workload(name, 1.0)
@@ -115,8 +127,19 @@ def main():
             out = torch.empty(1, dtype=torch.float64, device="cuda")
             info[name]["bytes_compulsory"] = int(w["bytes_compulsory"])
             calls[name] = (lambda e=w["expr"], x=x, u=u, v=v, a=w["agg"], o=out: F.fuse_outer(e, x, u, v, [], a, out=o))
-        del w
+        host[name] = w
+        outs[name] = out
         print("# %s inputs ready in %.1f s" % (name, time.perf_counter() - t0), file=sys.stderr, flush=True)
+
+    if args.probe:
+        n = 1 << 27                                   # 2^27 doubles = 1 GiB
+        src = torch.rand(n, dtype=torch.float64, device="cuda")
+        dst = torch.empty_like(src)
+        sink = torch.zeros(1, dtype=torch.float64, device="cuda")
+        F.probe_copy(dst, src, 2048)
+        F.probe_read(src, sink, 1024)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- warm-up (includes hipRTC compilation of the five bodies)
     t0 = time.perf_counter()
@@ -157,6 +180,7 @@ def main():
              "min_us": round(ts[0] * 1e3, 2), "median_us": round(ts[len(ts) // 2] * 1e3, 2),
              "GBps": round(gbps(info[name]["bytes"], avg * 1e-3), 1)}
         e["frac_of_hbm_peak"] = round(e["GBps"] / HBM_PEAK_GBPS, 4)
+        e["traffic"] = MEASURED_TRAFFIC_BYTES.get(name)
         if info[name]["nnz"]:
             e["nnz_per_s"] = round(info[name]["nnz"] / (avg * 1e-3), 1)
         if "bytes_compulsory" in info[name]:
@@ -177,12 +201,23 @@ def main():
             "seed": W.BASE_SEED},
         "roofline": {"bound": "hbm", "kernel": d["kernel"], "template": dominant, "achieved": d["GBps"],
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(d["GBps"] / HBM_PEAK_GBPS, 4),
-                     "traffic": None},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant)},
         "templates": templates,
         "plan_cache": {"hits": hits, "misses": misses, "compile_ms": round(compile_ms, 1)},
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = _cpu_baseline(names)
+        base, refs = _cpu_baseline(names, host)
+        result["cpu_baseline"] = base
+        # the same run also checks the GPU results against the oracle's
+        errs = {}
+        for name in names:
+            got, ref = outs[name].cpu().numpy(), refs[name]
+            if name == "magg":
+                errs[name] = float(np.max(np.abs(got - ref) / np.abs(ref)))
+            else:
+                errs[name] = float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+        result["max_rel_err_vs_oracle"] = {k: float("%.2e" % v) for k, v in errs.items()}
+        assert all(v <= 1e-10 for v in errs.values()), errs
     print(json.dumps(result), flush=True)
 
 

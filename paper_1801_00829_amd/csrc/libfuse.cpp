@@ -477,13 +477,14 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     const std::string key = std::string("rowcsr|") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(ac) + "|g" + std::to_string(G) + "c" + std::to_string(C) + "r" + std::to_string(RS) + "b" +
                             std::to_string(BLOCK) + "p" + std::to_string(npad) + "s" + std::to_string(stage_rv) +
-                            "w" + std::to_string(X->rowptr_is64 != 0) + std::to_string(m < (1LL << 30));
+                            "w" + std::to_string(X->rowptr_is64 != 0) + std::to_string(m < (1LL << 30)) + "nt" +
+                            std::to_string(env_int("FUSE_CSR_NT", 0));
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, "fuse_row_csr", [&](const std::string &name) {
         std::string s = kSrcArgs;
         // plain (cached) loads: the register slots of neighbouring rows overlap in
         // memory, so lines are re-used from cache rather than streamed once
-        s += "#define FUSE_NT 0\n";
+        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_CSR_NT", 0)) + "\n";
         s += kSrcCommon;
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
         s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_C " + std::to_string(C) +
