@@ -223,12 +223,20 @@ def outer(expr, rowptr, colidx, vals, shape, u, v, sides, agg):
     m, n = shape
     u = np.asarray(u, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
-    out = []
+    out, pos = [], []
     for i in range(m):
         for k in range(int(rowptr[i]), int(rowptr[i + 1])):
             j = int(colidx[k])
             d = math.fsum(float(u[i, t]) * float(v[j, t]) for t in range(u.shape[1]))
             out.append(_scalar_body(expr, float(vals[k]), sides, i, j, uvdot=d))
+            pos.append((i, j))
+    r = u.shape[1]
+    if agg == "right_mm":      # I_i += w_ij * V_j
+        return np.array([[math.fsum(w * float(v[j, t]) for w, (ii, j) in zip(out, pos) if ii == i)
+                          for t in range(r)] for i in range(m)]).reshape(m, r)
+    if agg == "left_mm":       # I_j += w_ij * U_i
+        return np.array([[math.fsum(w * float(u[i, t]) for w, (i, jj) in zip(out, pos) if jj == j)
+                          for t in range(r)] for j in range(n)]).reshape(n, r)
     if agg == "none":
         return np.array(out, dtype=np.float64)
     if agg == "full":

@@ -239,6 +239,32 @@ def csr_col_sums(x: Csr, a):
     return out
 
 
+def csr_matmul_dense(x: Csr, w, b):
+    """W %*% B with W stored on X's pattern (w = its nnz-vector) and dense B (n x r) -> m x r."""
+    m, n = x.shape
+    w = np.ascontiguousarray(_f64(w)).reshape(-1)
+    b, ldb = _rowmajor(b)
+    assert w.size == x.vals.size and b.shape[0] == n
+    o = np.empty((m, b.shape[1]), dtype=np.float64)
+    _c().oracle_csr_matmul_dense(_p(x.rowptr), _p(x.colidx), _p(w), _i(m), _p(b), _i(ldb), _i(b.shape[1]), _p(o))
+    return o
+
+
+def csr_t_matmul_dense(x: Csr, w, b):
+    """t(W) %*% B with W stored on X's pattern and dense B (m x r) -> n x r."""
+    m, n = x.shape
+    w = np.ascontiguousarray(_f64(w)).reshape(-1)
+    b, ldb = _rowmajor(b)
+    assert w.size == x.vals.size and b.shape[0] == m
+    r = b.shape[1]
+    o = np.empty((n, r), dtype=np.float64)
+    wk = _work(n * r)
+    base = (wk.ctypes.data + 15) & ~15
+    _c().oracle_csr_t_matmul_dense(_p(x.rowptr), _p(x.colidx), _p(w), _i(m), _i(n), _p(b), _i(ldb), _i(r),
+                                   _p(o), ctypes.c_void_p(base))
+    return o
+
+
 # ------------------------------------------------------------ CSR utilities ---
 
 def csr_row_index(x: Csr):

@@ -213,3 +213,40 @@ void oracle_csr_col_sums(const int64_t *rowptr, const int32_t *colidx, int64_t m
     for (int64_t j = 0; j < n; ++j)
         out[j] = (double)work[j];
 }
+
+/* O = W %*% B for a matrix W stored on a CSR pattern (w = its nnz values) and
+ * dense B (n x r, ld ldb): O[i,:] = sum over stored (i,j) of w_ij * B[j,:].
+ * With B = V this is the right-hand Outer product of Sec. 2.2 ("scale V_j by
+ * w_ij and add it to the output row I_i").  O is m x r, contiguous. */
+void oracle_csr_matmul_dense(const int64_t *rowptr, const int32_t *colidx, const double *w,
+                             int64_t m, const double *b, int64_t ldb, int64_t r, double *o)
+{
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t t = 0; t < r; ++t) {
+            acc_t s = 0.0L;
+            for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k)
+                s += (acc_t)w[k] * (acc_t)b[(int64_t)colidx[k] * ldb + t];
+            o[i * r + t] = (double)s;
+        }
+}
+
+/* O = t(W) %*% B for W on a CSR pattern (m rows, n columns) and dense B (m x r):
+ * O[j,:] = sum over stored (i,j) of w_ij * B[i,:]  (the left-hand Outer product).
+ * O is n x r, contiguous; work holds n*r extended-precision accumulators. */
+void oracle_csr_t_matmul_dense(const int64_t *rowptr, const int32_t *colidx, const double *w,
+                               int64_t m, int64_t n, const double *b, int64_t ldb, int64_t r,
+                               double *o, acc_t *work)
+{
+    for (int64_t x = 0; x < n * r; ++x)
+        work[x] = 0.0L;
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k) {
+            acc_t wk = (acc_t)w[k];
+            acc_t *dst = work + (int64_t)colidx[k] * r;
+            for (int64_t t = 0; t < r; ++t)
+                dst[t] += wk * (acc_t)b[i * ldb + t];
+        }
+    for (int64_t x = 0; x < n * r; ++x)
+        o[x] = (double)work[x];
+}

@@ -268,7 +268,11 @@ def outer(expr, x: ops.Csr, u, v, sides, agg):
     it): binds to every stored cell X_ij, the rows U_i and V_j and dense side
     inputs; the chain is evaluated over nnz-vectors, never over m x n.
 
-    agg "full" -> 1 value; "none" -> nnz-vector on X's pattern.
+    agg "full" -> 1 value; "none" -> nnz-vector on X's pattern;
+    "right_mm" -> m x r: the body values W (on X's pattern) times V, i.e. row i
+    accumulates w_ij * V_j (Sec. 2.2, paragraph after the Outer listing);
+    "left_mm" -> n x r: t(W) times U, i.e. row j accumulates w_ij * U_i (the
+    mirrored variant of Table 1).
     """
     m, n = x.shape
     rows = ops.csr_row_index(x)
@@ -310,4 +314,8 @@ def outer(expr, x: ops.Csr, u, v, sides, agg):
         return r
     if agg == "full":
         return np.array([ops.sum_full(r)])
+    if agg == "right_mm":
+        return ops.csr_matmul_dense(x, r, v)
+    if agg == "left_mm":
+        return ops.csr_t_matmul_dense(x, r, u)
     raise ValueError("unknown aggregation %r" % (agg,))

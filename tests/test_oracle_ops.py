@@ -137,3 +137,27 @@ def test_elementwise_ops_per_element():
     # outputs are fresh arrays (materialised intermediates), inputs untouched
     c = ops.ew_binary("add", a, 0.0)
     assert c is not a and not np.shares_memory(c, a)
+
+
+def test_csr_matmul_dense_both_sides_vs_scipy_and_brute_force():
+    m, n, r = 37, 29, 6
+    rowptr, colidx, vals = W.csr_bernoulli(m, n, 0.25, 13)
+    x = ops.make_csr(rowptr, colidx, vals, (m, n))
+    g = _rng(6)
+    w = g.normal(size=vals.size)
+    bv, bu = g.normal(size=(n, r)), g.normal(size=(m, r))
+    sw = sp.csr_matrix((w, colidx, rowptr), shape=(m, n))
+    np.testing.assert_allclose(ops.csr_matmul_dense(x, w, bv), sw @ bv, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(ops.csr_t_matmul_dense(x, w, bu), sw.T @ bu, rtol=1e-13, atol=1e-14)
+    # non-square shapes would not even match if the operands were swapped
+    assert ops.csr_matmul_dense(x, w, bv).shape == (m, r) and ops.csr_t_matmul_dense(x, w, bu).shape == (n, r)
+    rows = ops.csr_row_index(x)
+    i, t = 5, 3
+    ref = math.fsum(w[k] * bv[colidx[k], t] for k in range(vals.size) if rows[k] == i)
+    assert abs(ops.csr_matmul_dense(x, w, bv)[i, t] - ref) <= 4 * np.spacing(abs(ref)) + 1e-300
+    j = int(colidx[vals.size // 2])
+    ref = math.fsum(w[k] * bu[rows[k], t] for k in range(vals.size) if colidx[k] == j)
+    assert abs(ops.csr_t_matmul_dense(x, w, bu)[j, t] - ref) <= 4 * np.spacing(abs(ref)) + 1e-300
+    # leading dimension of B
+    bb = g.normal(size=(n, r + 4))
+    np.testing.assert_allclose(ops.csr_matmul_dense(x, w, bb[:, :r]), sw @ bb[:, :r], rtol=1e-13, atol=1e-14)

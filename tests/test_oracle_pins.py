@@ -330,3 +330,50 @@ def test_workload_plans_equal_generic_unfused_evaluation():
             b = unfused.outer(w["expr"], x, w["U"], w["V"], w["sides"], w["agg"])
         scale_ = np.abs(a).max() if a.size else 1.0
         assert np.abs(a - b).max() <= 1e-13 * scale_, name
+
+
+# ---------------------------------------------------- Outer right_mm / left_mm ---
+
+ALS_W = [("main",), ("neq0",), ("uvdot",), ("mul",)]        # (X != 0) * (U_i . V_j), Sec. 2.2 Outer listing
+
+
+def test_outer_mm_variants_closed_form_dense_formula_and_interp():
+    m, n, r = 17, 13, 5
+    g = _rng(10)
+    u, v = g.uniform(size=(m, r)), g.uniform(size=(n, r))
+    x = _csr(m, n, 0.3, 33)
+    d = ops.csr_to_dense(x)
+    # the ALS-CG update of Sec. 2.2 (first expression): ((X != 0) * (U t(V))) V, and its mirror image
+    ref_r = ((d != 0) * (u @ v.T)) @ v
+    ref_l = ((d != 0) * (u @ v.T)).T @ u
+    np.testing.assert_allclose(unfused.outer(ALS_W, x, u, v, [], "right_mm"), ref_r, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(unfused.outer(ALS_W, x, u, v, [], "left_mm"), ref_l, rtol=1e-12, atol=1e-13)
+    for agg in ("right_mm", "left_mm"):
+        np.testing.assert_allclose(unfused.outer(ALS_W, x, u, v, [], agg),
+                                   interp.outer(ALS_W, x.rowptr, x.colidx, x.vals, x.shape, u, v, [], agg),
+                                   rtol=1e-12, atol=1e-13)
+    # closed form: U = V = ones, body = X  ->  right: rowSums(X) in every column; left: colSums(X)
+    ones_u, ones_v = np.ones((m, r)), np.ones((n, r))
+    got = unfused.outer([("main",)], x, ones_u, ones_v, [], "right_mm")
+    np.testing.assert_allclose(got, np.repeat(d.sum(1)[:, None], r, 1), rtol=1e-14)
+    got = unfused.outer([("main",)], x, ones_u, ones_v, [], "left_mm")
+    np.testing.assert_allclose(got, np.repeat(d.sum(0)[:, None], r, 1), rtol=1e-14)
+    # rows / columns without stored cells give zero rows
+    empty = ops.make_csr(np.zeros(m + 1, np.int64), np.zeros(0, np.int32), np.zeros(0), (m, n))
+    assert not unfused.outer(ALS_W, empty, u, v, [], "right_mm").any()
+    assert unfused.outer(ALS_W, empty, u, v, [], "left_mm").shape == (n, r)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_outer_mm_expressions_unfused_equals_interp(seed):
+    rng = _rng(4500 + seed)
+    m, n, r = int(rng.integers(1, 7)), int(rng.integers(1, 7)), int(rng.integers(1, 5))
+    kinds = ["matrix", "colvec", "rowvec", "scalar"]
+    sides = _sides(rng, kinds, m, n)
+    x = _csr(m, n, 0.5, 4500 + seed)
+    u, v = rng.uniform(size=(m, r)), rng.uniform(size=(n, r))
+    expr = random_scalar_expr(rng, len(kinds), extra_leaf="uvdot")
+    for agg in ("right_mm", "left_mm"):
+        np.testing.assert_allclose(unfused.outer(expr, x, u, v, sides, agg),
+                                   interp.outer(expr, x.rowptr, x.colidx, x.vals, x.shape, u, v, sides, agg),
+                                   rtol=1e-11, atol=1e-12, equal_nan=True)
