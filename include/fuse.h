@@ -61,7 +61,9 @@ typedef enum {
     FUSE_AGG_FULL = 1,
     FUSE_AGG_ROW = 2,
     FUSE_AGG_COL = 3,
-    FUSE_AGG_COL_T = 4
+    FUSE_AGG_COL_T = 4,
+    FUSE_AGG_RIGHT_MM = 5,  /* Outer only */
+    FUSE_AGG_LEFT_MM = 6    /* Outer only */
 } fuse_agg;
 
 /* How a side input is addressed from cell (rix, cix) of the main input
@@ -180,8 +182,14 @@ int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
  * the CSR matrix X with MAIN = X_ij and UVDOT = U[i,:] . V[j,:]; U is
  * X->rows x r, V is X->cols x r; U %*% t(V) is never formed.  Side inputs are
  * dense and read at (i, j) / i / j.
- *   agg FULL : out[0] = sum over stored cells of body
- *   agg NONE : out[p] = body at stored cell p (nnz values on X's pattern)
+ *   agg FULL     : out[0] = sum over stored cells of body
+ *   agg NONE     : out[p] = body at stored cell p (nnz values on X's pattern)
+ *   agg RIGHT_MM : out is rows(X) x r, contiguous: out[i,:] = sum over the stored
+ *                  cells (i, j) of row i of body * V[j,:]  (the listing's
+ *                  vectMultAdd: "scale V_j by w_ij and add it to the output row")
+ *   agg LEFT_MM  : out is cols(X) x r, contiguous: out[j,:] = sum over the stored
+ *                  cells (i, j) of column j of body * U[i,:]  (the mirrored variant;
+ *                  accumulated with fp64 atomics: the order of additions is not fixed)
  * 1 <= r <= 1024. */
 int fuse_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
                const fuse_side *sides, int nsides, int agg, double *out, void *stream);

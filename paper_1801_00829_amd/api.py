@@ -4,7 +4,7 @@ from collections import namedtuple
 
 from . import _lib as L
 
-AGG = {"none": 0, "full": 1, "row": 2, "col": 3, "col_t": 4}
+AGG = {"none": 0, "full": 1, "row": 2, "col": 3, "col_t": 4, "right_mm": 5, "left_mm": 6}
 SIDE = {"matrix": 0, "colvec": 1, "rowvec": 2, "scalar": 3}
 OPS = {
     "main": 1, "side": 2, "const": 3, "uvdot": 4,
@@ -223,7 +223,8 @@ def fuse_outer(expr, X, U, V, sides=(), agg="full", out=None, stream=None):
     xs = _csr(X)
     ud, vd = _dense(U), _dense(V)
     sa, ns = _sides(list(sides), xs.rows, xs.cols)
-    out = _out(out, 1 if agg == "full" else xs.nnz, X.vals)
+    count = {"full": 1, "none": xs.nnz, "right_mm": xs.rows * ud.cols, "left_mm": xs.cols * ud.cols}[agg]
+    out = _out(out, count, X.vals)
     _check(lib.fuse_outer(ctypes.byref(e), ctypes.byref(xs), ctypes.byref(ud), ctypes.byref(vd), sa, ns,
                           AGG[agg], out.data_ptr(), _stream(stream)))
     return out

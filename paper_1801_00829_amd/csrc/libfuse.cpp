@@ -600,10 +600,22 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         return rc;
     if ((rc = check_dense(U, "U", launch)) || (rc = check_dense(V, "V", launch)))
         return rc;
-    if (agg != FUSE_AGG_FULL && agg != FUSE_AGG_NONE)
-        return fail(agg_code(agg) < 0 ? FUSE_EINVAL : FUSE_EUNSUPPORTED,
-                    "Outer supports FUSE_AGG_FULL and FUSE_AGG_NONE in this build");
-    if (launch && !out && (agg == FUSE_AGG_FULL || X->nnz > 0))
+    int mode;                      // 0 no_agg, 1 full_agg, 2 right_mm, 3 left_mm
+    switch (agg) {
+    case FUSE_AGG_NONE: mode = 0; break;
+    case FUSE_AGG_FULL: mode = 1; break;
+    case FUSE_AGG_RIGHT_MM: mode = 2; break;
+    case FUSE_AGG_LEFT_MM: mode = 3; break;
+    case FUSE_AGG_ROW:
+    case FUSE_AGG_COL:
+    case FUSE_AGG_COL_T:
+        return fail(FUSE_EUNSUPPORTED, "Outer has the variants no_agg, full_agg, right_mm and left_mm");
+    default:
+        return fail(FUSE_EINVAL, "unknown aggregation " + std::to_string(agg));
+    }
+    const int64_t out_count = mode == 0 ? X->nnz : mode == 1 ? 1 : mode == 2 ? X->rows * U->cols
+                                                                               : X->cols * U->cols;
+    if (launch && !out && out_count > 0)
         return fail(FUSE_EINVAL, "out is NULL");
     if (U->rows != X->rows || V->rows != X->cols || U->cols != V->cols)
         return fail(FUSE_ESHAPE, "Outer needs U: rows(X) x r and V: cols(X) x r");
@@ -654,8 +666,9 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     for (int q = 0; q < nsides; ++q)
         need_col |= prog.side_used[q] && (sides[q].kind == FUSE_SIDE_MATRIX || sides[q].kind == FUSE_SIDE_ROWVEC);
 
+    const bool out_vec = vec2 && (!launch || aligned16(out));
     const std::string key = std::string("outer|") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
-                            std::to_string(agg) + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
+                            std::to_string(mode) + (mode == 2 && out_vec ? "o" : "") + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
                             std::to_string(EPL) + "u" + std::to_string(UNR) + "b" + std::to_string(BLOCK) + "w" +
                             std::to_string(X->rowptr_is64 != 0);
     std::shared_ptr<Plan> plan;
@@ -666,8 +679,8 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
         s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_EPL " + std::to_string(EPL) +
              "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_UNR " + std::to_string(UNR) +
-             "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_FULL " +
-             std::to_string(agg == FUSE_AGG_FULL) + "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) +
+             "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_MODE " +
+             std::to_string(mode) + "\n#define FUSE_OUT_VEC " + std::to_string(out_vec) + "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) +
              "\n#define FUSE_NEED_COL " + std::to_string(need_col) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_outer_body(prog);
@@ -685,7 +698,9 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     if ((rc = rt.load(*plan, fn, g_err)))
         return rc;
     if (X->rows == 0 || X->nnz == 0)
-        return zero_fill(fn, out, agg == FUSE_AGG_FULL ? 1 : 0, stream);
+        return zero_fill(fn, out, mode == 0 ? 0 : out_count, stream);
+    if (mode == 3 && (rc = zero_fill(fn, out, out_count, stream)))
+        return rc;
     const int cus = rt.num_cus();
     const int NW = BLOCK / 64;
     int64_t gx = (X->rows + NW - 1) / NW;

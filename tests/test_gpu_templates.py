@@ -363,3 +363,82 @@ def test_outer_rowptr64_and_strided_factors():
     for rp64 in (False, True):
         got = host(F.fuse_outer(body, dev_csr(rp, ci, va, (m, n), rp64), to_dev(ub)[:, :r], to_dev(vb)[:, :r], [], "full"))
         assert_close(got, ref, what="outer strided rp64=%s" % rp64)
+
+
+# ------------------------------------------------- Outer right_mm / left_mm ---
+
+ALS_W = [("main",), ("neq0",), ("uvdot",), ("mul",)]        # (X != 0) * (U_i . V_j): the ALS-CG update, Sec. 2.2
+
+
+@pytest.mark.parametrize("agg", ["right_mm", "left_mm"])
+def test_outer_mm_on_all_patterns(agg):
+    import paper_1801_00829_amd as F
+    for name, (rp, ci, va), shape in _csr_cases():
+        m, n = shape
+        for r in (100, 7, 20):
+            print("outer", agg, name, shape, "rank", r, flush=True)
+            rng = np.random.default_rng(31)
+            u, v = rng.uniform(size=(m, r)), rng.uniform(size=(n, r))
+            x = ops.make_csr(rp, ci, va, shape)
+            got = host(F.fuse_outer(ALS_W, dev_csr(rp, ci, va, shape), to_dev(u), to_dev(v), [], agg))
+            ref = unfused.outer(ALS_W, x, u, v, [], agg)
+            assert_close(got, ref, scale=max(np.abs(ref).max(), 1e-300) if ref.size else 1.0, what="outer %s %s" % (agg, name))
+            # rows / columns without stored cells must be exactly zero
+            empty = (np.diff(rp) == 0) if agg == "right_mm" else (np.bincount(ci, minlength=n) == 0)
+            assert not got.reshape(-1, r)[empty].any()
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_outer_mm_random_expressions(case):
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(9500 + case)
+    m, n, r = [(1, 1, 1), (30, 20, 7), (200, 300, 100), (64, 64, 20)][case % 4]
+    dens = [1.0, 0.3, 0.02, 0.1][case % 4]
+    rp, ci, va = W.csr_bernoulli(m, n, dens, 9500 + case)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    u, v = rng.uniform(size=(m, r)), rng.uniform(size=(n, r))
+    sides = _sides(rng, m, n)
+    expr = random_scalar_expr(rng, len(KINDS), extra_leaf="uvdot")
+    xd, ud, vd, sd = dev_csr(rp, ci, va, (m, n)), to_dev(u), to_dev(v), dev_sides(sides)
+    w_abs = np.abs(np.nan_to_num(unfused.outer(expr, x, u, v, sides, "none"), nan=0, posinf=0, neginf=0))
+    for agg in ("right_mm", "left_mm"):
+        print("outer mm case", case, (m, n, r), agg, expr, flush=True)
+        got = host(F.fuse_outer(expr, xd, ud, vd, sd, agg))
+        ref = unfused.outer(expr, x, u, v, sides, agg)
+        scale = unfused.outer([("side", 0)], x, u, v, [("matrix", np.zeros((m, n)))], agg)   # shape only
+        absref = ops.csr_matmul_dense(x, w_abs, np.abs(v)) if agg == "right_mm" else ops.csr_t_matmul_dense(x, w_abs, np.abs(u))
+        assert_close(got, ref, scale=max(absref.max(initial=0.0), 1e-300), tol=1e-9, what="outer mm %s" % agg)
+
+
+def test_outer_right_mm_unaligned_output_and_odd_rank():
+    import torch
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(41)
+    m, n = 90, 70
+    rp, ci, va = W.csr_bernoulli(m, n, 0.1, 42)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    for r in (6, 5):
+        u, v = rng.uniform(size=(m, r)), rng.uniform(size=(n, r))
+        buf = torch.zeros(m * r + 1, dtype=torch.float64, device="cuda")
+        out = buf[1:]                                   # 8-byte aligned only
+        F.fuse_outer(ALS_W, dev_csr(rp, ci, va, (m, n)), to_dev(u), to_dev(v), [], "right_mm", out=out)
+        assert_close(host(out), unfused.outer(ALS_W, x, u, v, [], "right_mm"), what="right_mm unaligned r=%d" % r)
+
+
+def test_als_cg_update_as_two_fused_operators():
+    """O = ((X != 0) * (U t(V))) V + 1e-6 * U * r  (Sec. 2.2, first example expression): the Outer
+    right_mm operator followed by the Cell no_agg operator of the Cell listing."""
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(51)
+    m, n, r = 300, 200, 20
+    rp, ci, va = W.csr_bernoulli(m, n, 0.05, 52)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    u, v, rr = rng.uniform(size=(m, r)), rng.uniform(size=(n, r)), rng.uniform(size=m)
+    inner = F.fuse_outer(ALS_W, dev_csr(rp, ci, va, (m, n)), to_dev(u), to_dev(v), [], "right_mm").view(m, r)
+    cell = [("side", 0), ("main",), ("const", 1e-6), ("mul",), ("side", 1), ("mul",), ("add",)]   # I + U*1e-6*r
+    got = host(F.fuse_cell(cell, to_dev(u), [("matrix", inner), ("colvec", to_dev(rr))], "none")).reshape(m, r)
+    ref_inner = unfused.outer(ALS_W, x, u, v, [], "right_mm")
+    ref = unfused.cell(cell, u, [("matrix", ref_inner), ("colvec", rr)], "none")
+    assert_close(got, ref, what="ALS-CG update")
+    d = ops.csr_to_dense(x)
+    np.testing.assert_allclose(got, ((d != 0) * (u @ v.T)) @ v + 1e-6 * u * rr[:, None], rtol=1e-11)

@@ -144,7 +144,10 @@ def test_shape_and_argument_errors(F):
     assert lib.fuse_prepare_outer(ctypes.byref(e2), ctypes.byref(ok), ctypes.byref(L.Dense(None, 6, 3, 3)),
                                   ctypes.byref(L.Dense(None, 4, 3, 3)), None, 0, 1) == -2
     assert lib.fuse_prepare_outer(ctypes.byref(e2), ctypes.byref(ok), ctypes.byref(L.Dense(None, 4, 3, 3)),
-                                  ctypes.byref(L.Dense(None, 6, 3, 3)), None, 0, 2) == -7    # row agg: not built
+                                  ctypes.byref(L.Dense(None, 6, 3, 3)), None, 0, 2) == -7    # Outer has no row_agg
+    for mm in (5, 6):                                                                      # right_mm, left_mm
+        assert lib.fuse_prepare_outer(ctypes.byref(e2), ctypes.byref(ok), ctypes.byref(L.Dense(None, 4, 3, 3)),
+                                      ctypes.byref(L.Dense(None, 6, 3, 3)), None, 0, mm) == 0
 
 
 def test_row_type_checking_and_sparse_safety(F):
