@@ -153,6 +153,21 @@ int fuse_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_side *sides
 int fuse_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides,
               int nsides, double *out_k, void *stream);
 
+/* Cell and MAgg over a SPARSE main input (Fig. 8b / 8d; Sec. 5.2: the sparse
+ * matrix X is the "sparse driver" that makes the whole operator sparse-safe).
+ * The body is evaluated at the stored cells of the CSR matrix X only, with the
+ * dense side inputs read at the same positions; it must be sparse-safe, i.e. be
+ * zero wherever X has no stored cell (products with X, zero-preserving unaries,
+ * sums of such), otherwise FUSE_EDESC.
+ *   fuse_cell_csr: agg NONE -> nnz values on X's pattern; ROW -> rows(X) sums;
+ *                  COL / COL_T -> cols(X) sums (cols <= 6144); FULL -> 1 value.
+ *   fuse_magg_csr: k full aggregates in one scan of X; out_k[j] = sum of body j.
+ */
+int fuse_cell_csr(const fuse_expr *expr, const fuse_csr *X, const fuse_side *sides, int nsides,
+                  int agg, double *out, void *stream);
+int fuse_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_side *sides,
+                  int nsides, double *out_k, void *stream);
+
 /* Row template (Table 1, row "Row"; Sec. 2.2 Row listing; Fig. 1b / Fig. 8e-f
  * t(X) %*% (X %*% v)).  The body runs once per row of the main input, dense
  * (Xd) or CSR (Xs) -- exactly one of the two is non-NULL.  Values in the body
@@ -203,6 +218,10 @@ int fuse_prepare_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_sid
                       int nsides, int agg);
 int fuse_prepare_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides,
                       int nsides);
+int fuse_prepare_cell_csr(const fuse_expr *expr, const fuse_csr *X, const fuse_side *sides,
+                          int nsides, int agg);
+int fuse_prepare_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_side *sides,
+                          int nsides);
 int fuse_prepare_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
                      const fuse_side *sides, int nsides, int agg);
 int fuse_prepare_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U,

@@ -261,6 +261,21 @@ def row_csr(expr, x: ops.Csr, sides, agg):
     raise ValueError("unknown aggregation %r" % (agg,))
 
 
+def cell_csr(expr, x: ops.Csr, sides, agg):
+    """Cell template over a sparse main input (Fig. 8b; Sec. 5.2 "Cell Operations": X is
+    the sparse driver): the sparse-safe body is evaluated over nnz-vectors on X's
+    pattern -- a Row body without row aggregates.  Shapes as for ``row_csr``."""
+    for tok in expr:
+        if tok[0] in ("rowsum", "dot", "uvdot"):
+            raise ValueError("token %r is not valid in a Cell expression" % (tok,))
+    return row_csr(expr, x, sides, agg)
+
+
+def magg_csr(exprs, x: ops.Csr, sides):
+    """MAgg over a sparse main input (Fig. 8d): k full aggregates, each on its own."""
+    return np.array([cell_csr(e, x, sides, "full")[0] for e in exprs])
+
+
 # --------------------------------------------------------------------- Outer ---
 
 def outer(expr, x: ops.Csr, u, v, sides, agg):

@@ -58,11 +58,16 @@ def load():
     lib.fuse_magg.argtypes = [P(Expr), ci, P(Dense), P(Side), ci, vp, vp]
     lib.fuse_row.argtypes = [P(Expr), P(Dense), P(CsrDesc), P(Side), ci, ci, vp, vp]
     lib.fuse_outer.argtypes = [P(Expr), P(CsrDesc), P(Dense), P(Dense), P(Side), ci, ci, vp, vp]
+    lib.fuse_cell_csr.argtypes = [P(Expr), P(CsrDesc), P(Side), ci, ci, vp, vp]
+    lib.fuse_magg_csr.argtypes = [P(Expr), ci, P(CsrDesc), P(Side), ci, vp, vp]
+    lib.fuse_prepare_cell_csr.argtypes = [P(Expr), P(CsrDesc), P(Side), ci, ci]
+    lib.fuse_prepare_magg_csr.argtypes = [P(Expr), ci, P(CsrDesc), P(Side), ci]
     lib.fuse_prepare_cell.argtypes = [P(Expr), P(Dense), P(Side), ci, ci]
     lib.fuse_prepare_magg.argtypes = [P(Expr), ci, P(Dense), P(Side), ci]
     lib.fuse_prepare_row.argtypes = [P(Expr), P(Dense), P(CsrDesc), P(Side), ci, ci]
     lib.fuse_prepare_outer.argtypes = [P(Expr), P(CsrDesc), P(Dense), P(Dense), P(Side), ci, ci]
-    for f in (lib.fuse_cell, lib.fuse_magg, lib.fuse_row, lib.fuse_outer, lib.fuse_prepare_cell,
+    for f in (lib.fuse_cell_csr, lib.fuse_magg_csr, lib.fuse_prepare_cell_csr, lib.fuse_prepare_magg_csr,
+              lib.fuse_cell, lib.fuse_magg, lib.fuse_row, lib.fuse_outer, lib.fuse_prepare_cell,
               lib.fuse_prepare_magg, lib.fuse_prepare_row, lib.fuse_prepare_outer):
         f.restype = ci
     lib.fuse_last_error.restype = ctypes.c_char_p

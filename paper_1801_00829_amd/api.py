@@ -168,6 +168,46 @@ def fuse_magg(exprs, X, sides=(), out=None, stream=None):
     return out
 
 
+def fuse_cell_csr(expr, X, sides=(), agg="full", out=None, stream=None):
+    """C: fuse_cell_csr.  X: Csr of device tensors; sparse-safe Cell body at the stored cells."""
+    lib = L.load()
+    e, keep = _expr(expr)
+    xs = _csr(X)
+    sa, ns = _sides(list(sides), xs.rows, xs.cols)
+    out = _out(out, _agg_count(agg, xs.rows, xs.cols, True, nnz=xs.nnz), X.vals)
+    _check(lib.fuse_cell_csr(ctypes.byref(e), ctypes.byref(xs), sa, ns, AGG[agg], out.data_ptr(), _stream(stream)))
+    return out
+
+
+def fuse_magg_csr(exprs, X, sides=(), out=None, stream=None):
+    """C: fuse_magg_csr.  k full aggregates over the stored cells of X in one scan."""
+    lib = L.load()
+    pairs = [_expr(e) for e in exprs]
+    ea = (L.Expr * len(pairs))(*[p[0] for p in pairs])
+    xs = _csr(X)
+    sa, ns = _sides(list(sides), xs.rows, xs.cols)
+    out = _out(out, len(pairs), X.vals)
+    _check(lib.fuse_magg_csr(ea, len(pairs), ctypes.byref(xs), sa, ns, out.data_ptr(), _stream(stream)))
+    return out
+
+
+def prepare_cell_csr(expr, shape, nnz, sides=(), agg="full", rowptr64=False):
+    lib = L.load()
+    e, keep = _expr(expr)
+    xs = L.CsrDesc(None, None, None, int(rowptr64), shape[0], shape[1], int(nnz))
+    sa, ns = _sides([(k, v) for k, v in sides], shape[0], shape[1])
+    _check(lib.fuse_prepare_cell_csr(ctypes.byref(e), ctypes.byref(xs), sa, ns, AGG[agg]))
+
+
+def prepare_magg_csr(exprs, shape, nnz, sides=(), rowptr64=False):
+    lib = L.load()
+    pairs = [_expr(e) for e in exprs]
+    ea = (L.Expr * len(pairs))(*[p[0] for p in pairs])
+    xs = L.CsrDesc(None, None, None, int(rowptr64), shape[0], shape[1], int(nnz))
+    sa, ns = _sides([(k, v) for k, v in sides], shape[0], shape[1])
+    _check(lib.fuse_prepare_magg_csr(ea, len(pairs), ctypes.byref(xs), sa, ns))
+
+
 def _row_result_is_vector(expr, sides):
     """Kind of a Row body's result (only used to size the output of agg='none')."""
     st = []

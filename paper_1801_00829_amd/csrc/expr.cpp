@@ -139,9 +139,14 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
     if (row) {
         const Node &r = prog.nodes[prog.roots[0]];
         prog.result_vec = r.vec;
-        if (t == Tmpl::ROW_CSR && r.vec && !r.zp)
-            return fail(err, "not sparse-safe: the result vector is not zero where the main input has no "
-                             "stored cell");
+        for (int root : prog.roots) {
+            const Node &q = prog.nodes[root];
+            if (q.vec != r.vec)
+                return fail(err, "the results of a multi-aggregate must all be of the same kind");
+            if (t == Tmpl::ROW_CSR && q.vec && !q.zp)
+                return fail(err, "not sparse-safe: the result is not zero where the main input has no "
+                                 "stored cell");
+        }
         // order reductions by stage (= level of the reduction node - 1)
         int maxlvl = 0;
         for (const Node &n : prog.nodes)
@@ -279,6 +284,13 @@ std::string emit_row_body(const Program &prog)
     }
     src += "}\n";
     const int root = prog.roots[0];
+    src += "#define FUSE_KRES " + std::to_string(prog.roots.size()) + "\n";
+    src += "__device__ __forceinline__ void fuse_final_elems(double a, const double *sv, const double *rsc,\n"
+           "                                                 const double *red, double *r)\n{\n";
+    for (size_t j = 0; j < prog.roots.size(); ++j)
+        src += "    r[" + std::to_string(j) + "] = " +
+               (prog.result_vec ? em.gen(prog.roots[j]) : std::string("0.0")) + ";\n";
+    src += "}\n";
     src += "__device__ __forceinline__ double fuse_final_elem(double a, const double *sv, const double *rsc,\n"
            "                                                  const double *red)\n{\n    return " +
            (prog.result_vec ? em.gen(root) : std::string("0.0")) + ";\n}\n";

@@ -438,7 +438,7 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
 
 // ------------------------------------------------------------------------- row --
 int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides, int nsides, int agg,
-                 double *out, hipStream_t stream, bool launch)
+                 double *out, hipStream_t stream, bool launch, const char *name_prefix = "fuse_row_csr")
 {
     Runtime &rt = Runtime::get();
     const int64_t m = X->rows, n = X->cols;
@@ -480,7 +480,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
                             "w" + std::to_string(X->rowptr_is64 != 0) + std::to_string(m < (1LL << 30)) + "nt" +
                             std::to_string(env_int("FUSE_CSR_NT", 0));
     std::shared_ptr<Plan> plan;
-    int rc = rt.plan(key, "fuse_row_csr", [&](const std::string &name) {
+    int rc = rt.plan(key, name_prefix, [&](const std::string &name) {
         std::string s = kSrcArgs;
         // plain (cached) loads: the register slots of neighbouring rows overlap in
         // memory, so lines are re-used from cache rather than streamed once
@@ -509,7 +509,8 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     Plan::Loaded fn;
     if ((rc = rt.load(*plan, fn, g_err)))
         return rc;
-    const int64_t out_count = ac == 0 ? (prog.result_vec ? X->nnz : m) : ac == 1 ? 1 : ac == 2 ? m : n;
+    const int64_t out_count = ac == 0 ? (prog.result_vec ? X->nnz : m)
+                                      : ac == 1 ? (int64_t)prog.roots.size() : ac == 2 ? m : n;
     if (m == 0)
         return zero_fill(fn, out, out_count, stream);
 
@@ -519,7 +520,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     int64_t gx = (m + rows_per_iter - 1) / rows_per_iter;
     gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CSR_BLOCKS_PER_CU", 1)));
     Workspace ws;
-    const size_t need = ac == 3 ? (size_t)gx * (size_t)n : (size_t)gx;
+    const size_t need = ac == 3 ? (size_t)gx * (size_t)n : (size_t)gx * prog.roots.size();
     if ((rc = rt.workspace(stream, need, ws, g_err)))
         return rc;
     fuse_kargs A;
@@ -546,6 +547,45 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     if (ac == 3)
         return run_combine(fn, ws.partials, (int)gx, (int)n, out, stream);
     return 0;
+}
+
+// Cell / MAgg bodies over a CSR main input: the sparse-safe binding of the Cell
+// template (Sec. 2.2 "Template Types").  A Cell body is a Row body without row
+// aggregates, so it runs in the CSR Row skeleton; k > 1 results only with the
+// full aggregate (MAgg).
+int cell_csr_impl(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_side *sides, int nsides,
+                  int agg, double *out, void *stream_, bool launch, bool is_magg)
+{
+    g_err.clear();
+    if (!exprs)
+        return fail(FUSE_EINVAL, "expr is NULL");
+    if (k < 1 || k > FUSE_MAX_AGGS)
+        return fail(FUSE_EINVAL, "k must be in [1, " + std::to_string(FUSE_MAX_AGGS) + "]");
+    const int ac = agg_code(agg);
+    if (ac < 0)
+        return fail(FUSE_EINVAL, "unknown aggregation " + std::to_string(agg));
+    int rc = check_csr(X, launch);
+    if (rc)
+        return rc;
+    if (nsides < 0 || nsides > FUSE_MAX_SIDES || (nsides > 0 && !sides))
+        return fail(FUSE_EINVAL, "bad sides / nsides");
+    for (int q = 0; q < nsides; ++q)
+        if (sides[q].kind < 0 || sides[q].kind > 3)
+            return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
+    Program cprog, prog;
+    if ((rc = parse_program(Tmpl::CELL, exprs, k, sides, nsides, cprog, g_err)))     // Cell tokens only
+        return rc;
+    if ((rc = parse_program(Tmpl::ROW_CSR, exprs, k, sides, nsides, prog, g_err)))   // kinds + sparse-safety
+        return rc;
+    if (!prog.result_vec)
+        return fail(FUSE_EDESC, "not sparse-safe: the body does not depend on the main input");
+    if ((rc = check_sides(sides, nsides, X->rows, X->cols, launch, prog.side_used)))
+        return rc;
+    const int64_t count = ac == 1 ? k : ac == 2 ? X->rows : ac == 3 ? X->cols : X->nnz;
+    if (launch && !out && count > 0)
+        return fail(FUSE_EINVAL, "out is NULL");
+    return row_csr_impl(prog, X, sides, nsides, agg, out, (hipStream_t)stream_, launch,
+                        is_magg ? "fuse_magg_csr" : "fuse_cell_csr");
 }
 
 int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, const fuse_side *sides,
@@ -755,6 +795,28 @@ int fuse_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
                const fuse_side *sides, int nsides, int agg, double *out, void *stream)
 {
     return outer_impl(expr, X, U, V, sides, nsides, agg, out, stream, true);
+}
+
+int fuse_cell_csr(const fuse_expr *expr, const fuse_csr *X, const fuse_side *sides, int nsides, int agg,
+                  double *out, void *stream)
+{
+    return cell_csr_impl(expr, 1, X, sides, nsides, agg, out, stream, true, false);
+}
+
+int fuse_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_side *sides, int nsides,
+                  double *out_k, void *stream)
+{
+    return cell_csr_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, out_k, stream, true, true);
+}
+
+int fuse_prepare_cell_csr(const fuse_expr *expr, const fuse_csr *X, const fuse_side *sides, int nsides, int agg)
+{
+    return cell_csr_impl(expr, 1, X, sides, nsides, agg, nullptr, nullptr, false, false);
+}
+
+int fuse_prepare_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_side *sides, int nsides)
+{
+    return cell_csr_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, nullptr, nullptr, false, true);
 }
 
 int fuse_prepare_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_side *sides, int nsides, int agg)

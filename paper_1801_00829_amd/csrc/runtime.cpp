@@ -64,8 +64,11 @@ int Runtime::compile(Plan &p, std::string &err)
         err = std::string("hiprtcCreateProgram: ") + hiprtcGetErrorString(r);
         return FUSE_ECOMPILE;
     }
+    // -ffp-contract=off: a body rounds after every operator, exactly like the chain of
+    // basic operators it replaces (a*b+c is not silently turned into one fused
+    // multiply-add); the skeletons call fma() explicitly where they want one.
     const char *opts[] = {arch_opt.c_str(), "-O3", "-std=c++17", "-Xclang", "-target-feature",
-                          "-Xclang", "-packed-fp32-ops", "-munsafe-fp-atomics"};
+                          "-Xclang", "-packed-fp32-ops", "-munsafe-fp-atomics", "-ffp-contract=off"};
     r = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
     if (r != HIPRTC_SUCCESS) {
         size_t n = 0;

@@ -51,11 +51,12 @@ def random_scalar_expr(rng, n_sides, depth=4, leaves=("main", "side", "const"), 
     return build(depth)
 
 
-def random_row_expr(rng, side_kinds, depth=4, want="V", sparse_safe=False):
+def random_row_expr(rng, side_kinds, depth=4, want="V", sparse_safe=False, reductions=True):
     """Random Row expression producing a row vector ("V") or a per-row scalar ("S").
 
     ``side_kinds``: list of kinds of the side inputs.  With ``sparse_safe`` the
-    program stays zero-preserving w.r.t. the main input (usable on CSR rows).
+    program stays zero-preserving w.r.t. the main input (usable on CSR rows);
+    ``reductions=False`` leaves out rowsum / dot (a Cell body).
     """
     v_sides = [k for k, s in enumerate(side_kinds) if s in ("matrix", "rowvec")]
     s_sides = [k for k, s in enumerate(side_kinds) if s in ("colvec", "scalar")]
@@ -66,7 +67,7 @@ def random_row_expr(rng, side_kinds, depth=4, want="V", sparse_safe=False):
             if s_sides and rng.random() < 0.5:
                 return [("side", int(s_sides[rng.integers(len(s_sides))]))]
             return [("const", float(np.round(rng.uniform(-2, 2), 3)))]
-        p = rng.random()
+        p = rng.random() if reductions else 0.4 + 0.6 * rng.random()
         if p < 0.4:
             a, _ = vector(d - 1, zp=sparse_safe)
             if rng.random() < 0.5:

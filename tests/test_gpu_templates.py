@@ -442,3 +442,72 @@ def test_als_cg_update_as_two_fused_operators():
     assert_close(got, ref, what="ALS-CG update")
     d = ops.csr_to_dense(x)
     np.testing.assert_allclose(got, ((d != 0) * (u @ v.T)) @ v + 1e-6 * u * rr[:, None], rtol=1e-11)
+
+
+@pytest.mark.parametrize("nops", [1, 8, 40])
+def test_row_long_chain_expression(nops):
+    """sum(f(X / rowSums(X))) with f a chain of `nops` scalar multiplications (the expression of
+    the instruction-footprint experiment, Sec. 5.2): one reduction stage, then a long body."""
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(61)
+    m, n = 257, 1000
+    x = rng.uniform(0.5, 1.5, size=(m, n))
+    expr = [("main",), ("main",), ("rowsum",), ("div",)]
+    for i in range(1, nops + 1):
+        expr += [("const", 1.0 + 1.0 / (i + 1)), ("mul",)]
+    got = host(F.fuse_row(expr, to_dev(x), [], "full"))
+    assert_close(got, unfused.row_dense(expr, x, [], "full"), what="chain %d" % nops)
+    got = host(F.fuse_row(expr, to_dev(x), [], "none"))
+    assert_close(got, unfused.row_dense(expr, x, [], "none"), what="chain %d none" % nops)
+
+
+# ------------------------------------------------- Cell / MAgg over a sparse X ---
+
+@pytest.mark.parametrize("case", range(10))
+def test_sparse_cell_and_magg_random_expressions(case):
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(9700 + case)
+    m, n = [(1, 1), (37, 19), (300, 1000), (1000, 100), (64, 3000)][case % 5]
+    dens = [1.0, 0.3, 0.1, 0.02, 0.004][case % 5]
+    rp, ci, va = W.csr_bernoulli(m, n, dens, 9700 + case)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    sides = _sides(rng, m, n)
+    xd, sd = dev_csr(rp, ci, va, (m, n)), dev_sides(sides)
+    exprs = [random_row_expr(rng, KINDS, depth=3, want="V", sparse_safe=True, reductions=False) for _ in range(3)]
+    for agg in ("none", "row", "col", "full"):
+        print("sparse cell case", case, (m, n), agg, exprs[0], flush=True)
+        got = host(F.fuse_cell_csr(exprs[0], xd, sd, agg))
+        ref = unfused.cell_csr(exprs[0], x, sides, agg)
+        a = np.abs(np.nan_to_num(unfused.cell_csr(exprs[0], x, sides, "none"), nan=0, posinf=0, neginf=0))
+        scale = {"none": None, "full": a.sum(), "row": ops.csr_row_sums(x, a).max(initial=0.0),
+                 "col": ops.csr_col_sums(x, a).max(initial=0.0)}[agg]
+        assert_close(got, ref, scale=None if scale is None else max(scale, 1e-300), what="sparse cell %s" % agg)
+    got = host(F.fuse_magg_csr(exprs, xd, sd))
+    ref = unfused.magg_csr(exprs, x, sides)
+    for j in range(3):
+        a = np.abs(np.nan_to_num(unfused.cell_csr(exprs[j], x, sides, "none"), nan=0, posinf=0, neginf=0))
+        assert_close(got[j], ref[j], scale=max(a.sum(), 1e-300), what="sparse magg[%d]" % j)
+        one = host(F.fuse_cell_csr(exprs[j], xd, sd, "full"))
+        assert_close(got[j], one[0], scale=max(a.sum(), 1e-300), tol=1e-13, what="sparse magg vs cell [%d]" % j)
+
+
+def test_sparse_cell_paper_expression_and_rejections():
+    """sum(X * Y * Z) with a sparse X (density 0.1) and dense Y, Z: equals the dense operator
+    on the densified X; bodies that are not sparse-safe are rejected."""
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(81)
+    m, n = 2000, 1000
+    rp, ci, va = W.csr_bernoulli(m, n, 0.1, 82)
+    y, z = rng.uniform(size=(2, m, n))
+    xd = dev_csr(rp, ci, va, (m, n))
+    expr = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+    sd = [("matrix", to_dev(y)), ("matrix", to_dev(z))]
+    got = host(F.fuse_cell_csr(expr, xd, sd, "full"))
+    dense = ops.csr_to_dense(ops.make_csr(rp, ci, va, (m, n)))
+    from oracle import plans
+    assert_close(got, plans.cell_sum_xyz(dense, y, z), what="sparse sum(XYZ)")
+    assert_close(got, host(F.fuse_cell(expr, to_dev(dense), sd, "full")), tol=1e-12, what="sparse vs dense operator")
+    for bad in ([("main",), ("const", 1.0), ("add",)], [("side", 0)]):
+        with pytest.raises(F.FuseError) as e:
+            F.fuse_cell_csr(bad, xd, sd, "full")
+        assert e.value.code == -3

@@ -377,3 +377,43 @@ def test_random_outer_mm_expressions_unfused_equals_interp(seed):
         np.testing.assert_allclose(unfused.outer(expr, x, u, v, sides, agg),
                                    interp.outer(expr, x.rowptr, x.colidx, x.vals, x.shape, u, v, sides, agg),
                                    rtol=1e-11, atol=1e-12, equal_nan=True)
+
+
+# ----------------------------------------------------- Cell / MAgg over sparse X ---
+
+@pytest.mark.parametrize("seed", range(12))
+def test_sparse_cell_equals_dense_cell_on_the_densified_input(seed):
+    """Sparse-safe bodies: restricting the evaluation to the stored cells of X does not
+    change any aggregate (Sec. 1: sparse drivers), checked against the dense Cell evaluators."""
+    rng = _rng(5000 + seed)
+    m, n = int(rng.integers(1, 8)), int(rng.integers(1, 9))
+    kinds = ["matrix", "colvec", "rowvec", "scalar"]
+    sides = _sides(rng, kinds, m, n)
+    x = _csr(m, n, 0.4, 5000 + seed)
+    d = ops.csr_to_dense(x)
+    expr = random_row_expr(rng, kinds, depth=3, want="V", sparse_safe=True, reductions=False)
+    for agg in ("full", "row", "col"):
+        got = unfused.cell_csr(expr, x, sides, agg)
+        np.testing.assert_allclose(got, unfused.cell(expr, d, sides, agg), rtol=1e-11, atol=1e-12, equal_nan=True)
+        np.testing.assert_allclose(got, interp.cell(expr, d, sides, agg), rtol=1e-11, atol=1e-12, equal_nan=True)
+    got = np.zeros((m, n))
+    got[ops.csr_row_index(x), x.colidx] = unfused.cell_csr(expr, x, sides, "none")
+    np.testing.assert_allclose(got, unfused.cell(expr, d, sides, "none"), rtol=1e-12, atol=1e-13, equal_nan=True)
+
+
+def test_sparse_magg_closed_form_and_dense_equivalence():
+    m, n = 40, 30
+    x = _csr(m, n, 0.1, 71)
+    r = _rng(72)
+    y, z = r.uniform(-1, 1, size=(2, m, n))
+    exprs = [[("main",), ("side", 0), ("mul",)], [("main",), ("side", 1), ("mul",)], [("main",), ("pow2",)]]
+    sides = [("matrix", y), ("matrix", z)]
+    got = unfused.magg_csr(exprs, x, sides)
+    np.testing.assert_allclose(got, plans.magg_xy_xz_xx(ops.csr_to_dense(x), y, z), rtol=1e-13)
+    rows = ops.csr_row_index(x)
+    ref = [math.fsum(x.vals * y[rows, x.colidx]), math.fsum(x.vals * z[rows, x.colidx]), math.fsum(x.vals ** 2)]
+    np.testing.assert_allclose(got, ref, rtol=1e-14)
+    with pytest.raises(ValueError):
+        unfused.cell_csr([("main",), ("const", 1.0), ("add",)], x, sides, "full")
+    with pytest.raises(ValueError):
+        unfused.cell_csr([("main",), ("rowsum",)], x, sides, "full")
