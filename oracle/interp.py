@@ -145,30 +145,53 @@ def _row_body(expr, xi, cols, n_cols, sides, i):
             kind = sides[tok[1]][0]
             if kind in ("matrix", "rowvec"):
                 st.append(("V", {j: _side_at(sides, tok[1], i, j) for j in cols}))
+            elif kind == "rhs":
+                st.append(("M", np.asarray(sides[tok[1]][1], dtype=np.float64)))
+            elif kind == "kvec":
+                st.append(("K", [float(t) for t in np.asarray(sides[tok[1]][1], dtype=np.float64)[i]]))
             else:
                 st.append(("S", _side_at(sides, tok[1], i, 0)))
         elif name == "const":
             st.append(("S", float(tok[1])))
         elif name in _UN:
             k, a = st.pop()
-            st.append((k, {j: _u(name, v) for j, v in a.items()} if k == "V" else _u(name, a)))
+            if k == "V":
+                st.append((k, {j: _u(name, v) for j, v in a.items()}))
+            elif k == "K":
+                st.append((k, [_u(name, v) for v in a]))
+            else:
+                st.append((k, _u(name, a)))
         elif name in _BI:
             kb, b = st.pop()
             ka, a = st.pop()
             if ka == "S" and kb == "S":
                 st.append(("S", _b(name, a, b)))
+            elif "K" in (ka, kb):
+                assert "V" not in (ka, kb)
+                kk = len(a) if ka == "K" else len(b)
+                st.append(("K", [_b(name, a[t] if ka == "K" else a, b[t] if kb == "K" else b) for t in range(kk)]))
             else:
                 st.append(("V", {j: _b(name, a[j] if ka == "V" else a, b[j] if kb == "V" else b)
                                  for j in cols}))
         elif name == "rowsum":
             k, a = st.pop()
-            assert k == "V"
-            st.append(("S", math.fsum(a.values())))
+            assert k in ("V", "K")
+            st.append(("S", math.fsum(a.values() if k == "V" else a)))
         elif name == "dot":
             kb, b = st.pop()
             ka, a = st.pop()
-            assert ka == "V" and kb == "V"
-            st.append(("S", math.fsum(a[j] * b[j] for j in cols)))
+            assert ka == kb and ka in ("V", "K")
+            st.append(("S", math.fsum(a[j] * b[j] for j in (cols if ka == "V" else range(len(a))))))
+        elif name == "matmult":       # vectMatMult: row vector times the n x k right-hand side
+            kb, b = st.pop()
+            ka, a = st.pop()
+            assert ka == "V" and kb == "M"
+            st.append(("K", [math.fsum(a[j] * float(b[j, t]) for j in cols) for t in range(b.shape[1])]))
+        elif name == "outerk":        # vectOuterMultAdd: row (x) k-vector
+            kb, b = st.pop()
+            ka, a = st.pop()
+            assert ka == "V" and kb == "K"
+            st.append(("VK", (a, b)))
         else:
             raise ValueError(tok)
     assert len(st) == 1
@@ -200,6 +223,21 @@ def _row_aggregate(res, m, n, agg):
     if m == 0:
         return {"none": np.zeros((0, n)), "full": np.zeros(1), "row": np.zeros(0)}.get(agg, np.zeros(n))
     kind = res[0][0]
+    if kind == "K":
+        kk = len(res[0][1])
+        if agg == "none":
+            return np.array([r[1] for r in res]).reshape(m, kk)
+        if agg in ("col", "col_t"):
+            return np.array([math.fsum(r[1][t] for r in res) for t in range(kk)])
+        if agg == "full":
+            return np.array([math.fsum(v for r in res for v in r[1])])
+        raise ValueError(agg)
+    if kind == "VK":
+        kk = len(res[0][1][1])
+        if agg not in ("col", "col_t"):
+            raise ValueError(agg)
+        return np.array([[math.fsum(r[1][0][j] * r[1][1][t] for r in res) for t in range(kk)]
+                         for j in range(n)]).reshape(n, kk)
     if kind == "S":
         if agg == "none":
             return np.array([r[1] for r in res])

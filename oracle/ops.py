@@ -167,6 +167,26 @@ def t_matvec(x, q):
     return out
 
 
+def matmul(a, b):
+    """A %*% B for dense A (m x n) and B (n x k) -> m x k."""
+    a, lda = _rowmajor(a)
+    b, ldb = _rowmajor(b)
+    assert a.shape[1] == b.shape[0]
+    c = np.empty((a.shape[0], b.shape[1]), dtype=np.float64)
+    _c().oracle_matmul(_p(a), _i(a.shape[0]), _i(a.shape[1]), _i(lda), _p(b), _i(b.shape[1]), _i(ldb), _p(c))
+    return c
+
+
+def t_matmul(a, q):
+    """t(A) %*% Q for dense A (m x n) and Q (m x k) -> n x k."""
+    a, lda = _rowmajor(a)
+    q, ldq = _rowmajor(q)
+    assert a.shape[0] == q.shape[0]
+    c = np.empty((a.shape[1], q.shape[1]), dtype=np.float64)
+    _c().oracle_t_matmul(_p(a), _i(a.shape[0]), _i(a.shape[1]), _i(lda), _p(q), _i(q.shape[1]), _i(ldq), _p(c))
+    return c
+
+
 def _work(n):
     return np.zeros(int(n) * int(_c().oracle_acc_size()) + 16, dtype=np.uint8)
 

@@ -250,3 +250,34 @@ void oracle_csr_t_matmul_dense(const int64_t *rowptr, const int32_t *colidx, con
     for (int64_t x = 0; x < n * r; ++x)
         o[x] = (double)work[x];
 }
+
+/* C = A %*% B for dense A (m x n, ld lda) and B (n x k, ld ldb); C is m x k, contiguous.
+ * (X %*% V of the matrix-matrix chain of Fig. 8g; vectMatMult per row.) */
+void oracle_matmul(const double *a, int64_t m, int64_t n, int64_t lda, const double *b, int64_t k,
+                   int64_t ldb, double *c)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < m; ++i)
+        for (int64_t j = 0; j < k; ++j) {
+            acc_t s = 0.0L;
+            for (int64_t t = 0; t < n; ++t)
+                s += (acc_t)a[i * lda + t] * (acc_t)b[t * ldb + j];
+            c[i * k + j] = (double)s;
+        }
+}
+
+/* C = t(A) %*% Q for dense A (m x n, ld lda) and Q (m x k, ld ldq); C is n x k, contiguous.
+ * (t(X) %*% (...) of Fig. 8g and of the multinomial-logistic-regression core, Sec. 2.2, second
+ * example expression; vectOuterMultAdd per row.) */
+void oracle_t_matmul(const double *a, int64_t m, int64_t n, int64_t lda, const double *q, int64_t k,
+                     int64_t ldq, double *c)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n; ++t)
+        for (int64_t j = 0; j < k; ++j) {
+            acc_t s = 0.0L;
+            for (int64_t i = 0; i < m; ++i)
+                s += (acc_t)a[i * lda + t] * (acc_t)q[i * ldq + j];
+            c[t * k + j] = (double)s;
+        }
+}

@@ -58,3 +58,19 @@ def outer_sum_x_log_uv_dense(x_dense, u, v, eps=1e-15):
     d2 = ops.ew_unary("log", d1)
     d3 = ops.ew_binary("mul", x_dense, d2)
     return np.array([ops.sum_full(d3)])
+
+
+def row_tx_xv_matrix(x, v):
+    """t(X) %*% (X %*% V) with an n x k right-hand side (Fig. 8g): two matrix products."""
+    return ops.t_matmul(x, ops.matmul(x, v))
+
+
+def mlogreg_core(x, v, p):
+    """The inner-loop core of multinomial logistic regression (Sec. 2.2, second example):
+    Q = P * (X %*% V);  H = t(X) %*% (Q - P * rowSums(Q)), operator by operator."""
+    xv = ops.matmul(x, v)
+    q = ops.ew_binary("mul", p, xv)
+    rs = ops.row_sums(q).reshape(-1, 1)
+    t1 = ops.ew_binary("mul", p, rs)
+    t2 = ops.ew_binary("sub", q, t1)
+    return ops.t_matmul(x, t2)

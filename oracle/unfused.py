@@ -13,11 +13,16 @@ Expressions are symbolic postfix lists of tuples:
     ("const", c)         literal scalar
     ("uvdot",)           Outer only: U[i,:] . V[j,:] at the stored cell (i, j)
     (name,)              element-wise unary / binary operator, see ``oracle.ops``
-    ("rowsum",)          Row only: sum over the columns of a row vector
-    ("dot",)             Row only: inner product of two row vectors
+    ("rowsum",)          Row only: sum over the columns of a row vector (or over the
+                         entries of a k-vector)
+    ("dot",)             Row only: inner product of two row vectors (or two k-vectors)
+    ("matmult",)         Row only: row vector times a "rhs" side (n x k) -> k-vector
+    ("outerk",)          Row only, last token: row vector (x) k-vector, an n x k
+                         matrix per row that is summed over the rows (col / col_t)
 Side inputs are ``(kind, array)`` pairs with kind in
     "matrix" (m x n), "colvec" (m, indexed by row), "rowvec" (n, indexed by
-    column), "scalar".
+    column), "scalar", and for Row bodies "rhs" (n x k, the right-hand side of
+    "matmult") and "kvec" (m x k: one k-vector per row).
 Aggregation variants (Table 1): "none", "full", "row", "col", "col_t".
 """
 import numpy as np
@@ -106,50 +111,108 @@ def magg(exprs, x, sides):
 def row_dense(expr, x, sides, agg):
     """Row template over a dense main input (Table 1; Sec. 2.2 Row listing).
 
-    Values are row vectors ("V": broadcastable to m x n) or per-row scalars
-    ("S": shape (m,1) or ()).  Returns an array shaped by the variant:
-    none -> m x n (V) or m (S); row -> m; col / col_t -> n; full -> 1.
+    Values are row vectors ("V": broadcastable to m x n), per-row scalars ("S":
+    shape (m,1) or ()), per-row k-vectors ("K": m x k; products with an n x k
+    right-hand side, vectMatMult) or the right-hand side itself ("M").  Returns an
+    array shaped by the variant and the kind of the result:
+      V: none -> m x n; row -> m; col / col_t -> n; full -> 1
+      S: none -> m; full -> 1
+      K: none -> m x k; col / col_t -> k (sums over the rows); full -> 1
+      row (x) k-vector ("outerk"): col / col_t -> n x k = t(V-part) %*% K-part
+         (vectOuterMultAdd; the COL_AGG_B1_T variant of the Row listing)
     """
     x = np.asarray(x, dtype=np.float64)
     m, n = x.shape
     st = []   # (kind, array)
-    for tok in expr:
+    outer = None
+    for pos, tok in enumerate(expr):
         name = tok[0]
+        if outer is not None:
+            raise ValueError("outerk must be the last token")
         if name == "main":
             st.append(("V", x))
         elif name == "side":
             kind, arr = sides[tok[1]]
-            a = _side_dense(kind, arr, m, n)
-            st.append(("V" if kind in ("matrix", "rowvec") else "S", a))
+            if kind == "rhs":
+                a = np.asarray(arr, dtype=np.float64)
+                assert a.ndim == 2 and a.shape[0] == n
+                st.append(("M", a))
+            elif kind == "kvec":
+                a = np.asarray(arr, dtype=np.float64)
+                assert a.ndim == 2 and a.shape[0] == m
+                st.append(("K", a))
+            else:
+                a = _side_dense(kind, arr, m, n)
+                st.append(("V" if kind in ("matrix", "rowvec") else "S", a))
         elif name == "const":
             st.append(("S", np.float64(tok[1])))
         elif name in ops.UNARY_NAMES:
             k, a = st.pop()
+            if k == "M":
+                raise ValueError("a right-hand side can only be consumed by matmult")
             st.append((k, ops.ew_unary(name, a)))
         elif name in ops.BINARY_NAMES:
             kb, b = st.pop()
             ka, a = st.pop()
-            st.append(("V" if "V" in (ka, kb) else "S", ops.ew_binary(name, a, b)))
+            kinds = {ka, kb}
+            if "M" in kinds or kinds == {"V", "K"}:
+                raise ValueError("operands of %r do not conform" % name)
+            st.append(("V" if "V" in kinds else "K" if "K" in kinds else "S", ops.ew_binary(name, a, b)))
         elif name == "rowsum":
             k, a = st.pop()
-            if k != "V":
+            if k == "K":
+                st.append(("S", ops.row_sums(np.array(a)).reshape(m, 1)))
+            elif k == "V":
+                full = np.array(np.broadcast_to(a, (m, n)))
+                st.append(("S", ops.row_sums(full).reshape(m, 1)))
+            else:
                 raise ValueError("rowsum of a scalar")
-            full = np.array(np.broadcast_to(a, (m, n)))
-            st.append(("S", ops.row_sums(full).reshape(m, 1)))
         elif name == "dot":
             kb, b = st.pop()
             ka, a = st.pop()
-            if ka != "V" or kb != "V":
-                raise ValueError("dot needs two row vectors")
-            t = np.array(np.broadcast_to(ops.ew_binary("mul", a, b), (m, n)))
-            st.append(("S", ops.row_sums(t).reshape(m, 1)))
+            if ka == "K" and kb == "K":
+                st.append(("S", ops.row_sums(ops.ew_binary("mul", a, b)).reshape(m, 1)))
+            elif ka == "V" and kb == "V":
+                t = np.array(np.broadcast_to(ops.ew_binary("mul", a, b), (m, n)))
+                st.append(("S", ops.row_sums(t).reshape(m, 1)))
+            else:
+                raise ValueError("dot needs two row vectors or two k-vectors")
+        elif name == "matmult":
+            kb, b = st.pop()
+            ka, a = st.pop()
+            if ka != "V" or kb != "M":
+                raise ValueError("matmult needs a row vector and a right-hand side")
+            st.append(("K", ops.matmul(np.array(np.broadcast_to(a, (m, n))), b)))
+        elif name == "outerk":
+            kb, b = st.pop()
+            ka, a = st.pop()
+            if ka != "V" or kb != "K":
+                raise ValueError("outerk needs a row vector and a k-vector")
+            outer = (np.array(np.broadcast_to(a, (m, n))), np.array(b))
         else:
             raise ValueError("token %r is not valid in a Row expression" % (tok,))
+    if outer is not None:
+        if st:
+            raise ValueError("expression leaves values on the stack")
+        if agg not in ("col", "col_t"):
+            raise ValueError("a row (x) k-vector result needs the column aggregate")
+        return ops.t_matmul(outer[0], outer[1])
     if len(st) != 1:
         raise ValueError("expression leaves %d values on the stack" % len(st))
     kind, r = st[0]
+    if kind == "M":
+        raise ValueError("a right-hand side is not a result")
     if kind == "V":
         return _aggregate_dense(r, m, n, agg)
+    if kind == "K":
+        r = np.array(r, dtype=np.float64)
+        if agg == "none":
+            return r
+        if agg in ("col", "col_t"):
+            return ops.col_sums(r)
+        if agg == "full":
+            return np.array([ops.sum_full(r)])
+        raise ValueError("aggregation %r is not defined for a k-vector result" % (agg,))
     per_row = np.array(np.broadcast_to(np.asarray(r).reshape(-1, 1) if np.ndim(r) else r, (m, 1)),
                        dtype=np.float64).reshape(m)
     if agg == "none":

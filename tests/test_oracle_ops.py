@@ -161,3 +161,21 @@ def test_csr_matmul_dense_both_sides_vs_scipy_and_brute_force():
     # leading dimension of B
     bb = g.normal(size=(n, r + 4))
     np.testing.assert_allclose(ops.csr_matmul_dense(x, w, bb[:, :r]), sw @ bb[:, :r], rtol=1e-13, atol=1e-14)
+
+
+def test_matmul_and_t_matmul():
+    r = _rng(7)
+    a, b, q = r.normal(size=(31, 17)), r.normal(size=(17, 4)), r.normal(size=(31, 3))
+    np.testing.assert_allclose(ops.matmul(a, b), a @ b, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(ops.t_matmul(a, q), a.T @ q, rtol=1e-13, atol=1e-14)
+    assert ops.matmul(a, b).shape == (31, 4) and ops.t_matmul(a, q).shape == (17, 3)
+    ref = math.fsum(a[5, t] * b[t, 2] for t in range(17))
+    assert abs(ops.matmul(a, b)[5, 2] - ref) <= 4 * np.spacing(abs(ref))
+    ref = math.fsum(a[i, 9] * q[i, 1] for i in range(31))
+    assert abs(ops.t_matmul(a, q)[9, 1] - ref) <= 4 * np.spacing(abs(ref))
+    # views with leading dimensions
+    ab, bb = r.normal(size=(31, 20)), r.normal(size=(17, 6))
+    np.testing.assert_allclose(ops.matmul(ab[:, 2:19], bb[:, 1:5]), ab[:, 2:19] @ bb[:, 1:5], rtol=1e-13, atol=1e-14)
+    # a k = 1 right-hand side reduces to the matrix-vector routines
+    np.testing.assert_allclose(ops.matmul(a, b[:, :1]).ravel(), ops.matvec(a, b[:, 0]), rtol=0, atol=0)
+    np.testing.assert_allclose(ops.t_matmul(a, q[:, :1]).ravel(), ops.t_matvec(a, q[:, 0]), rtol=0, atol=0)

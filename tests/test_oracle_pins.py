@@ -417,3 +417,48 @@ def test_sparse_magg_closed_form_and_dense_equivalence():
         unfused.cell_csr([("main",), ("const", 1.0), ("add",)], x, sides, "full")
     with pytest.raises(ValueError):
         unfused.cell_csr([("main",), ("rowsum",)], x, sides, "full")
+
+
+# ------------------------------------------- Row with a matrix right-hand side ---
+
+MLOG_Q = [("side", 1), ("main",), ("side", 0), ("matmult",), ("mul",)]                   # Q = P * (X V)
+MLOGREG = [("main",)] + MLOG_Q + [("side", 1)] + MLOG_Q + [("rowsum",), ("mul",), ("sub",), ("outerk",)]
+TXXV = [("main",), ("main",), ("side", 0), ("matmult",), ("outerk",)]                     # t(X) (X V)
+
+
+def test_row_matrix_rhs_plans_numpy_interp_and_reductions():
+    r = _rng(11)
+    m, n, k = 60, 9, 4
+    x, v, p = r.normal(size=(m, n)), r.normal(size=(n, k)), r.uniform(size=(m, k))
+    sides = [("rhs", v), ("kvec", p)]
+    ref = x.T @ (x @ v)
+    np.testing.assert_allclose(plans.row_tx_xv_matrix(x, v), ref, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(unfused.row_dense(TXXV, x, sides, "col_t"), ref, rtol=1e-12, atol=1e-12)
+    q = p * (x @ v)
+    ref2 = x.T @ (q - p * q.sum(1, keepdims=True))
+    np.testing.assert_allclose(plans.mlogreg_core(x, v, p), ref2, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(unfused.row_dense(MLOGREG, x, sides, "col_t"), plans.mlogreg_core(x, v, p), rtol=1e-13, atol=1e-13)
+    xs, ps = x[:6], p[:6]
+    for expr in (TXXV, MLOGREG):
+        np.testing.assert_allclose(unfused.row_dense(expr, xs, [("rhs", v), ("kvec", ps)], "col_t"),
+                                   interp.row(expr, xs, [("rhs", v), ("kvec", ps)], "col_t"), rtol=1e-12, atol=1e-13)
+    # k = 1 reduces to the matrix-vector chain of the Row workload
+    np.testing.assert_allclose(unfused.row_dense(TXXV, x, [("rhs", v[:, :1])], "col_t").ravel(),
+                               plans.row_tx_w_xv(x, v[:, 0], np.ones(m)), rtol=1e-13, atol=1e-13)
+    # k-vector results: X V itself, its column sums, its total, rowSums(Q) per row
+    xv = [("main",), ("side", 0), ("matmult",)]
+    np.testing.assert_allclose(unfused.row_dense(xv, x, sides, "none"), x @ v, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(unfused.row_dense(xv, x, sides, "col"), (x @ v).sum(0), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(unfused.row_dense(xv, x, sides, "full"), [(x @ v).sum()], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(unfused.row_dense(MLOG_Q + [("rowsum",)], x, sides, "none"), q.sum(1), rtol=1e-12, atol=1e-13)
+    for agg in ("none", "col", "full"):
+        np.testing.assert_allclose(unfused.row_dense(xv, xs, sides[:1], agg), interp.row(xv, xs, sides[:1], agg), rtol=1e-12, atol=1e-13)
+    # ill-formed programs
+    for bad in ([("main",), ("side", 1), ("mul",)],                      # row vector (n) times k-vector
+                [("side", 0), ("abs",)],                                 # element-wise on the right-hand side
+                TXXV + [("abs",)],                                       # outerk must be last
+                [("side", 1), ("side", 0), ("matmult",)]):               # k-vector times right-hand side
+        with pytest.raises(ValueError):
+            unfused.row_dense(bad, x, sides, "col_t")
+    with pytest.raises(ValueError):
+        unfused.row_dense(TXXV, x, sides, "full")
