@@ -72,8 +72,13 @@ typedef enum {
     FUSE_SIDE_MATRIX = 0,   /* rows x cols as the main input, value at (rix, cix)     */
     FUSE_SIDE_COLVEC = 1,   /* `rows` values, value at rix  (data[rix * ld])          */
     FUSE_SIDE_ROWVEC = 2,   /* `cols` values, value at cix  (data[cix], contiguous)   */
-    FUSE_SIDE_SCALAR = 3    /* host scalar in `scalar`; passed as a kernel argument   */
+    FUSE_SIDE_SCALAR = 3,   /* host scalar in `scalar`; passed as a kernel argument   */
+    /* Row bodies over a dense main input only (Sec. 2.2 Row listing, vectMatMult / getVector): */
+    FUSE_SIDE_RHS = 4,      /* cols(X) x k right-hand side of FUSE_OP_MATMULT, 1 <= k <= 16 */
+    FUSE_SIDE_KVEC = 5      /* rows(X) x k: row rix is a k-vector (data[rix * ld + j])       */
 } fuse_side_kind;
+
+#define FUSE_MAX_K 16
 
 typedef struct {
     const double *data;     /* device pointer                                         */
@@ -117,8 +122,15 @@ typedef enum {
     FUSE_OP_POW,
     FUSE_OP_LT, FUSE_OP_LE, FUSE_OP_GT, FUSE_OP_GE, FUSE_OP_EQ, FUSE_OP_NE, /* 1.0 / 0.0 */
     /* Row template only: row vector -> per-row scalar */
-    FUSE_OP_ROWSUM = 48,    /* sum over the columns of a row vector  (vectSum)        */
-    FUSE_OP_DOT = 49        /* inner product of two row vectors      (dotProduct)     */
+    FUSE_OP_ROWSUM = 48,    /* sum over the columns of a row vector, or over the
+                               entries of a k-vector                  (vectSum)        */
+    FUSE_OP_DOT = 49,       /* inner product of two row vectors / two k-vectors (dotProduct) */
+    /* Row template over a dense main input only */
+    FUSE_OP_MATMULT = 50,   /* pops a RHS side, then a row vector; pushes the k-vector
+                               row %*% RHS                             (vectMatMult)    */
+    FUSE_OP_OUTERK = 51     /* last token: pops a k-vector, then a row vector; the result is
+                               the n x k matrix t(row) %*% kvec of every row, summed over
+                               the rows with FUSE_AGG_COL / COL_T  (vectOuterMultAdd)   */
 } fuse_op;
 
 typedef struct {
@@ -178,6 +190,14 @@ int fuse_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
  *                   (Xs); ROW -> m row sums; COL / COL_T -> n column sums
  *                   (t(X) %*% q is the body `X_i * q_i` with COL_T); FULL -> 1.
  *   scalar result:  NONE -> m values; FULL -> 1; others FUSE_EDESC.
+ *   k-vector result (dense input; products with a FUSE_SIDE_RHS, FUSE_SIDE_KVEC sides;
+ *                   element-wise operators work per component, scalars broadcast):
+ *                   NONE -> m x k; COL / COL_T -> k sums over the rows; FULL -> 1.
+ *   OUTERK result:  COL / COL_T -> out is n x k, contiguous: sum over the rows of
+ *                   t(row vector) %*% k-vector.  t(X) %*% (X %*% V) is the body
+ *                   MAIN, MAIN, SIDE V, MATMULT, OUTERK  (Fig. 8g); the core of multinomial
+ *                   logistic regression (Sec. 2.2, second example) is one such body too.
+ *                   Limit of this build: ceil(n / 64 / 2) * 2 * k <= 48.
  * For CSR input the body must be sparse-safe (Sec. 2.2 "Template Types": a
  * sparse-safe template binds only to the non-zeros): every vector that is
  * aggregated or returned must be zero wherever X has no stored cell (products

@@ -5,14 +5,14 @@ from collections import namedtuple
 from . import _lib as L
 
 AGG = {"none": 0, "full": 1, "row": 2, "col": 3, "col_t": 4, "right_mm": 5, "left_mm": 6}
-SIDE = {"matrix": 0, "colvec": 1, "rowvec": 2, "scalar": 3}
+SIDE = {"matrix": 0, "colvec": 1, "rowvec": 2, "scalar": 3, "rhs": 4, "kvec": 5}
 OPS = {
     "main": 1, "side": 2, "const": 3, "uvdot": 4,
     "neg": 16, "abs": 17, "sqrt": 18, "exp": 19, "log": 20, "pow2": 21, "sign": 22, "neq0": 23,
     "sigmoid": 24,
     "add": 32, "sub": 33, "mul": 34, "div": 35, "min": 36, "max": 37, "pow": 38,
     "lt": 39, "le": 40, "gt": 41, "ge": 42, "eq": 43, "ne": 44,
-    "rowsum": 48, "dot": 49,
+    "rowsum": 48, "dot": 49, "matmult": 50, "outerk": 51,
 }
 
 Csr = namedtuple("Csr", "rowptr colidx vals shape")
@@ -74,6 +74,11 @@ def _sides(sides, m, n):
         arr[k].kind = SIDE[kind]
         if kind == "scalar":
             arr[k].scalar = float(val)
+        elif kind in ("rhs", "kvec"):
+            if isinstance(val, tuple):                    # shape only: (rows, k)
+                arr[k].m = L.Dense(None, int(val[0]), int(val[1]), int(val[1]))
+            else:
+                arr[k].m = _dense(val)
         elif kind == "colvec":
             if isinstance(val, tuple) or val is None:
                 arr[k].m = L.Dense(None, m, 1, 1)
@@ -208,29 +213,49 @@ def prepare_magg_csr(exprs, shape, nnz, sides=(), rowptr64=False):
     _check(lib.fuse_prepare_magg_csr(ea, len(pairs), ctypes.byref(xs), sa, ns))
 
 
-def _row_result_is_vector(expr, sides):
-    """Kind of a Row body's result (only used to size the output of agg='none')."""
-    st = []
+def _row_result_kind(expr, sides):
+    """Kind of a Row body's result and k (only used to size the output): "S", "V", "K" or "VK"."""
+    st, kdim = [], 1
     for t in expr:
         name = t[0]
         if name == "main":
-            st.append(True)
+            st.append("V")
         elif name == "side":
-            st.append(sides[t[1]][0] in ("matrix", "rowvec"))
+            kind, val = sides[t[1]]
+            if kind in ("rhs", "kvec"):
+                kdim = int(val[1]) if isinstance(val, tuple) else int(val.shape[1])
+            st.append({"matrix": "V", "rowvec": "V", "rhs": "M", "kvec": "K"}.get(kind, "S"))
         elif name == "const":
-            st.append(False)
+            st.append("S")
         elif name == "rowsum":
             st.pop()
-            st.append(False)
+            st.append("S")
         elif name == "dot":
             st.pop()
             st.pop()
-            st.append(False)
+            st.append("S")
+        elif name == "matmult":
+            st.pop()
+            st.pop()
+            st.append("K")
+        elif name == "outerk":
+            st.pop()
+            st.pop()
+            st.append("VK")
         elif OPS.get(name, 0) >= 32:
             b = st.pop()
             a = st.pop()
-            st.append(a or b)
-    return bool(st and st[-1])
+            st.append("V" if "V" in (a, b) else "K" if "K" in (a, b) else "S")
+    return (st[-1] if st else "S"), kdim
+
+
+def _row_count(agg, m, n, expr, sides, nnz=None):
+    kind, k = _row_result_kind(expr, sides)
+    if kind == "VK":
+        return n * k
+    if kind == "K":
+        return {"none": m * k, "full": 1}.get(agg, k)
+    return _agg_count(agg, m, n, kind == "V", nnz=nnz)
 
 
 def fuse_row(expr, X, sides=(), agg="col_t", out=None, stream=None):
@@ -242,14 +267,14 @@ def fuse_row(expr, X, sides=(), agg="col_t", out=None, stream=None):
         xs = _csr(X)
         m, n = xs.rows, xs.cols
         sa, ns = _sides(sides, m, n)
-        cnt = _agg_count(agg, m, n, _row_result_is_vector(expr, sides), nnz=xs.nnz)
+        cnt = _row_count(agg, m, n, expr, sides, nnz=xs.nnz)
         out = _out(out, cnt, X.vals)
         _check(lib.fuse_row(ctypes.byref(e), None, ctypes.byref(xs), sa, ns, AGG[agg], out.data_ptr(),
                             _stream(stream)))
     else:
         xd = _dense(X)
         sa, ns = _sides(sides, xd.rows, xd.cols)
-        cnt = _agg_count(agg, xd.rows, xd.cols, _row_result_is_vector(expr, sides))
+        cnt = _row_count(agg, xd.rows, xd.cols, expr, sides)
         out = _out(out, cnt, X)
         _check(lib.fuse_row(ctypes.byref(e), ctypes.byref(xd), None, sa, ns, AGG[agg], out.data_ptr(),
                             _stream(stream)))

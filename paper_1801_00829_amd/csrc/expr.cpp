@@ -3,6 +3,8 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <map>
+#include <tuple>
 
 namespace fuse {
 
@@ -40,6 +42,18 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
 {
     const bool row = (t == Tmpl::ROW_DENSE || t == Tmpl::ROW_CSR);
     prog = Program();
+    std::map<std::tuple<int, int, uint64_t, int, int>, int> seen;   // hash-consing of sub-expressions
+    auto intern = [&](const Node &nd) {
+        uint64_t bits;
+        std::memcpy(&bits, &nd.imm, sizeof bits);
+        const auto key = std::make_tuple(nd.op, nd.arg, bits, nd.a, nd.b);
+        auto it = seen.find(key);
+        if (it != seen.end())
+            return it->second;
+        prog.nodes.push_back(nd);
+        seen[key] = (int)prog.nodes.size() - 1;
+        return (int)prog.nodes.size() - 1;
+    };
     for (int x = 0; x < k; ++x) {
         const fuse_expr &e = exprs[x];
         if (e.ntoks <= 0 || e.ntoks > 4096 || !e.toks) {
@@ -52,16 +66,31 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
             const std::string at = "expression " + std::to_string(x) + ", token " + std::to_string(i) + ": ";
             Node nd;
             nd.op = tk.op;
+            if (!st.empty() && prog.nodes[st.back()].kind == KIND_VK)
+                return fail(err, at + "OUTERK must be the last token of a body");
             if (tk.op == FUSE_OP_MAIN) {
-                nd.vec = row;
+                nd.kind = row ? KIND_V : KIND_S;
                 nd.zp = true;
             } else if (tk.op == FUSE_OP_SIDE) {
                 if (tk.arg < 0 || tk.arg >= nsides)
                     return fail(err, at + "side index " + std::to_string(tk.arg) + " out of range");
                 nd.arg = tk.arg;
                 const int kind = sides[tk.arg].kind;
-                nd.vec = row && (kind == FUSE_SIDE_MATRIX || kind == FUSE_SIDE_ROWVEC);
-                nd.zp = false;
+                if (kind == FUSE_SIDE_RHS || kind == FUSE_SIDE_KVEC) {
+                    if (t != Tmpl::ROW_DENSE)
+                        return fail(err, at + "right-hand-side and k-vector side inputs are only valid in a "
+                                              "Row body over a dense main input");
+                    const int kd = (int)sides[tk.arg].m.cols;
+                    if (kd < 1 || kd > FUSE_MAX_K)
+                        return fail(err, at + "k (columns of the side input) must be in [1, " +
+                                             std::to_string(FUSE_MAX_K) + "]");
+                    if (prog.kdim && prog.kdim != kd)
+                        return fail(err, at + "all k-vectors of a body must have the same length");
+                    prog.kdim = kd;
+                    nd.kind = kind == FUSE_SIDE_RHS ? KIND_M : KIND_K;
+                } else {
+                    nd.kind = (row && (kind == FUSE_SIDE_MATRIX || kind == FUSE_SIDE_ROWVEC)) ? KIND_V : KIND_S;
+                }
                 prog.side_used[tk.arg] = true;
             } else if (tk.op == FUSE_OP_CONST) {
                 nd.imm = tk.imm;
@@ -74,9 +103,11 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
                 nd.a = st.back();
                 st.pop_back();
                 const Node &a = prog.nodes[nd.a];
-                nd.vec = a.vec;
+                if (a.kind == KIND_M)
+                    return fail(err, at + "a right-hand side can only be consumed by MATMULT");
+                nd.kind = a.kind;
                 nd.level = a.level;
-                nd.zp = a.vec && a.zp && zero_preserving_unary(tk.op);
+                nd.zp = a.kind == KIND_V && a.zp && zero_preserving_unary(tk.op);
             } else if (is_binary(tk.op)) {
                 if (st.size() < 2)
                     return fail(err, at + "binary operator needs two operands");
@@ -85,10 +116,15 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
                 nd.a = st.back();
                 st.pop_back();
                 const Node &a = prog.nodes[nd.a], &b = prog.nodes[nd.b];
-                nd.vec = a.vec || b.vec;
+                if (a.kind == KIND_M || b.kind == KIND_M)
+                    return fail(err, at + "a right-hand side can only be consumed by MATMULT");
+                if ((a.kind == KIND_V && b.kind == KIND_K) || (a.kind == KIND_K && b.kind == KIND_V))
+                    return fail(err, at + "a row vector and a k-vector do not conform");
+                nd.kind = (a.kind == KIND_V || b.kind == KIND_V) ? KIND_V
+                          : (a.kind == KIND_K || b.kind == KIND_K) ? KIND_K : KIND_S;
                 nd.level = a.level > b.level ? a.level : b.level;
-                if (nd.vec) {
-                    const bool za = a.vec && a.zp, zb = b.vec && b.zp;
+                if (nd.kind == KIND_V) {
+                    const bool za = a.kind == KIND_V && a.zp, zb = b.kind == KIND_V && b.zp;
                     if (tk.op == FUSE_OP_MUL)
                         nd.zp = za || zb;
                     else if (tk.op == FUSE_OP_ADD || tk.op == FUSE_OP_SUB)
@@ -111,60 +147,104 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
                 nd.a = st.back();
                 st.pop_back();
                 const Node &a = prog.nodes[nd.a];
-                bool z = a.zp;
                 int lvl = a.level;
-                if (!a.vec || (nd.b >= 0 && !prog.nodes[nd.b].vec))
-                    return fail(err, at + "row aggregate of a scalar");
-                if (nd.b >= 0) {
-                    z = z || prog.nodes[nd.b].zp;
-                    if (prog.nodes[nd.b].level > lvl)
-                        lvl = prog.nodes[nd.b].level;
+                if (nd.b >= 0 && prog.nodes[nd.b].level > lvl)
+                    lvl = prog.nodes[nd.b].level;
+                if (a.kind == KIND_K && (nd.b < 0 || prog.nodes[nd.b].kind == KIND_K)) {
+                    // sum over the k entries of a per-row k-vector: plain scalar arithmetic
+                    nd.kind = KIND_S;
+                    nd.level = lvl;
+                } else {
+                    bool z = a.zp;
+                    if (a.kind != KIND_V || (nd.b >= 0 && prog.nodes[nd.b].kind != KIND_V))
+                        return fail(err, at + "row aggregate needs row vectors (or k-vectors)");
+                    if (nd.b >= 0)
+                        z = z || prog.nodes[nd.b].zp;
+                    if (t == Tmpl::ROW_CSR && !z)
+                        return fail(err, at + "not sparse-safe: row aggregate of a vector that is not zero "
+                                              "where the main input has no stored cell");
+                    nd.kind = KIND_S;
+                    nd.level = lvl + 1;
                 }
-                if (t == Tmpl::ROW_CSR && !z)
-                    return fail(err, at + "not sparse-safe: row aggregate of a vector that is not zero "
-                                          "where the main input has no stored cell");
-                nd.vec = false;
-                nd.level = lvl + 1;
+            } else if (tk.op == FUSE_OP_MATMULT) {
+                if (t != Tmpl::ROW_DENSE)
+                    return fail(err, at + "MATMULT is only valid in a Row body over a dense main input");
+                if (st.size() < 2)
+                    return fail(err, at + "MATMULT needs a row vector and a right-hand side");
+                nd.b = st.back();
+                st.pop_back();
+                nd.a = st.back();
+                st.pop_back();
+                const Node &a = prog.nodes[nd.a], &b = prog.nodes[nd.b];
+                if (a.kind != KIND_V || b.kind != KIND_M)
+                    return fail(err, at + "MATMULT needs a row vector and a right-hand side");
+                nd.kind = KIND_K;
+                nd.arg = b.arg;             // the right-hand side's side index
+                nd.level = a.level + 1;
+            } else if (tk.op == FUSE_OP_OUTERK) {
+                if (t != Tmpl::ROW_DENSE)
+                    return fail(err, at + "OUTERK is only valid in a Row body over a dense main input");
+                if (st.size() < 2)
+                    return fail(err, at + "OUTERK needs a row vector and a k-vector");
+                nd.b = st.back();
+                st.pop_back();
+                nd.a = st.back();
+                st.pop_back();
+                const Node &a = prog.nodes[nd.a], &b = prog.nodes[nd.b];
+                if (a.kind != KIND_V || b.kind != KIND_K)
+                    return fail(err, at + "OUTERK needs a row vector and a k-vector");
+                nd.kind = KIND_VK;
+                nd.level = a.level > b.level ? a.level : b.level;
             } else {
                 return fail(err, at + "unknown opcode " + std::to_string(tk.op));
             }
-            prog.nodes.push_back(nd);
-            st.push_back((int)prog.nodes.size() - 1);
+            nd.vec = nd.kind == KIND_V;
+            st.push_back(intern(nd));
         }
         if (st.size() != 1)
             return fail(err, "expression " + std::to_string(x) + " leaves " + std::to_string(st.size()) +
                                  " values on the stack");
+        if (prog.nodes[st.back()].kind == KIND_M)
+            return fail(err, "a right-hand side is not a result");
         prog.roots.push_back(st.back());
     }
     if (row) {
         const Node &r = prog.nodes[prog.roots[0]];
-        prog.result_vec = r.vec;
+        prog.result_vec = r.kind == KIND_V;
+        prog.result_kind = r.kind;
         for (int root : prog.roots) {
             const Node &q = prog.nodes[root];
-            if (q.vec != r.vec)
+            if (q.kind != r.kind)
                 return fail(err, "the results of a multi-aggregate must all be of the same kind");
-            if (t == Tmpl::ROW_CSR && q.vec && !q.zp)
+            if (t == Tmpl::ROW_CSR && q.kind == KIND_V && !q.zp)
                 return fail(err, "not sparse-safe: the result is not zero where the main input has no "
                                  "stored cell");
         }
-        // order reductions by stage (= level of the reduction node - 1)
+        if (prog.roots.size() > 1 && r.kind != KIND_V)
+            return fail(err, "several results need row-vector bodies");
+        // order the cross-lane reductions by stage (= level of the reduction node - 1)
+        auto is_red = [&](const Node &n) {
+            return n.op == FUSE_OP_MATMULT ||
+                   ((n.op == FUSE_OP_ROWSUM || n.op == FUSE_OP_DOT) && prog.nodes[n.a].kind == KIND_V);
+        };
         int maxlvl = 0;
         for (const Node &n : prog.nodes)
-            if (n.op == FUSE_OP_ROWSUM || n.op == FUSE_OP_DOT)
+            if (is_red(n))
                 maxlvl = n.level > maxlvl ? n.level : maxlvl;
         prog.nstage = maxlvl;
         for (int s = 0; s < maxlvl; ++s) {
             for (size_t i = 0; i < prog.nodes.size(); ++i) {
                 Node &n = prog.nodes[i];
-                if ((n.op == FUSE_OP_ROWSUM || n.op == FUSE_OP_DOT) && n.level == s + 1) {
-                    n.red = (int)prog.reductions.size();
+                if (is_red(n) && n.level == s + 1) {
+                    n.red = prog.nred;
+                    prog.nred += n.op == FUSE_OP_MATMULT ? prog.kdim : 1;
                     prog.reductions.push_back((int)i);
                 }
             }
-            prog.red_end.push_back((int)prog.reductions.size());
+            prog.red_end.push_back(prog.nred);
         }
-        if (prog.reductions.size() > 32)
-            return fail(err, "more than 32 row aggregates in one body");
+        if (prog.nred > 64)
+            return fail(err, "more than 64 row-aggregate slots in one body");
     }
     return FUSE_OK;
 }
@@ -174,7 +254,7 @@ std::string program_key(const Program &prog)
     std::string k;
     char buf[64];
     for (const Node &n : prog.nodes) {
-        std::snprintf(buf, sizeof buf, "%d.%d.%a;", n.op, n.arg, n.op == FUSE_OP_CONST ? n.imm : 0.0);
+        std::snprintf(buf, sizeof buf, "%d.%d.%a.%d.%d;", n.op, n.arg, n.op == FUSE_OP_CONST ? n.imm : 0.0, n.a, n.b);
         k += buf;
     }
     k += "|";
@@ -186,26 +266,42 @@ std::string program_key(const Program &prog)
 namespace {
 
 // Emits node `id` as a C expression.  `vec_side`/`scal_side`: names of the
-// arrays that hold vector-kind and scalar-kind side values; reductions that are
-// already available are read from red[]; `d` is the Outer inner product.
+// arrays that hold vector-kind and scalar-kind side values; cross-lane
+// reductions that are already available are read from red[]; `d` is the Outer
+// inner product.  For k-vector nodes `j` selects the component.
 struct Emitter {
     const Program &p;
     const char *vec_side;
     const char *scal_side;
-    std::string gen(int id) const
+    std::string gen(int id, int j = 0) const
     {
         const Node &n = p.nodes[id];
         switch (n.op) {
         case FUSE_OP_MAIN: return "a";
-        case FUSE_OP_SIDE: return std::string(n.vec ? vec_side : scal_side) + "[" + std::to_string(n.arg) + "]";
+        case FUSE_OP_SIDE:
+            if (n.kind == KIND_K)
+                return "kv[" + std::to_string(n.arg * FUSE_MAX_K + j) + "]";
+            return std::string(n.kind == KIND_V ? vec_side : scal_side) + "[" + std::to_string(n.arg) + "]";
         case FUSE_OP_CONST: return lit(n.imm);
         case FUSE_OP_UVDOT: return "d";
+        case FUSE_OP_MATMULT: return "red[" + std::to_string(n.red + j) + "]";
         case FUSE_OP_ROWSUM:
-        case FUSE_OP_DOT: return "red[" + std::to_string(n.red) + "]";
+        case FUSE_OP_DOT:
+            if (n.red >= 0)
+                return "red[" + std::to_string(n.red) + "]";
+            {   // over the k entries of k-vectors: written out
+                std::string sum = "(";
+                for (int c = 0; c < p.kdim; ++c) {
+                    if (c)
+                        sum += " + ";
+                    sum += n.op == FUSE_OP_DOT ? "(" + gen(n.a, c) + " * " + gen(n.b, c) + ")" : gen(n.a, c);
+                }
+                return sum + ")";
+            }
         default: break;
         }
         if (n.b < 0) {
-            const std::string x = gen(n.a);
+            const std::string x = gen(n.a, j);
             switch (n.op) {
             case FUSE_OP_NEG: return "(-" + x + ")";
             case FUSE_OP_ABS: return "fabs(" + x + ")";
@@ -218,7 +314,7 @@ struct Emitter {
             case FUSE_OP_SIGMOID: return "fuse_sigmoid(" + x + ")";
             }
         }
-        const std::string x = gen(n.a), y = gen(n.b);
+        const std::string x = gen(n.a, j), y = gen(n.b, j);
         switch (n.op) {
         case FUSE_OP_ADD: return "(" + x + " + " + y + ")";
         case FUSE_OP_SUB: return "(" + x + " - " + y + ")";
@@ -257,45 +353,80 @@ std::string emit_outer_body(const Program &prog)
            "    return " + em.gen(prog.roots[0]) + ";\n}\n";
 }
 
+// Row bodies.  Arguments of the generated functions:
+//   a    the main input's value at the current element of the row
+//   sv   values of the vector-kind side inputs at that element        [FUSE_NSIDES]
+//   kb   rows of the right-hand sides at that element's column        [FUSE_NSIDES * FUSE_MAX_K]
+//   rsc  per-row scalars (column-vector and scalar sides)             [FUSE_NSIDES]
+//   kv   per-row k-vectors (KVEC sides)                               [FUSE_NSIDES * FUSE_MAX_K]
+//   red  finished cross-lane reductions of earlier stages             [FUSE_NRED]
 std::string emit_row_body(const Program &prog)
 {
     Emitter em{prog, "sv", "rsc"};
+    const int kd = prog.kdim > 0 ? prog.kdim : 1;
+    const int kres = prog.result_kind == KIND_VK || prog.result_kind == KIND_K ? kd : (int)prog.roots.size();
     std::string src;
     src += "#define FUSE_NSTAGE " + std::to_string(prog.nstage) + "\n";
-    src += "#define FUSE_NRED " + std::to_string(prog.reductions.size()) + "\n";
+    src += "#define FUSE_NRED " + std::to_string(prog.nred) + "\n";
     src += "#define FUSE_RESULT_VEC " + std::string(prog.result_vec ? "1" : "0") + "\n";
+    src += "#define FUSE_RESULT_KIND " + std::to_string(prog.result_kind) + "\n";
+    src += "#define FUSE_KDIM " + std::to_string(kd) + "\n";
+    src += "#define FUSE_KRES " + std::to_string(kres) + "\n";
     src += "static __device__ constexpr int fuse_red_end[] = {";
     for (int e : prog.red_end)
         src += std::to_string(e) + ", ";
     src += "0};\n";
-    // one partial-sum update per reduction, grouped by stage
-    src += "__device__ __forceinline__ void fuse_stage(int st, double a, const double *sv, const double *rsc,\n"
-           "                                           const double *red, double *part)\n{\n";
-    int begin = 0;
+    // one partial-sum update per reduction slot, grouped by stage
+    src += "__device__ __forceinline__ void fuse_stage(int st, double a, const double *sv, const double *kb,\n"
+           "                                           const double *rsc, const double *kv, const double *red,\n"
+           "                                           double *part)\n{\n";
     for (int s = 0; s < prog.nstage; ++s) {
         src += "    if (st == " + std::to_string(s) + ") {\n";
-        for (int i = begin; i < prog.red_end[s]; ++i) {
-            const Node &n = prog.nodes[prog.reductions[i]];
-            std::string term = n.op == FUSE_OP_DOT ? "(" + em.gen(n.a) + " * " + em.gen(n.b) + ")" : em.gen(n.a);
-            src += "        part[" + std::to_string(i) + "] += " + term + ";\n";
+        for (int id : prog.reductions) {
+            const Node &n = prog.nodes[id];
+            if (n.level != s + 1)
+                continue;
+            if (n.op == FUSE_OP_MATMULT) {
+                src += "        { const double t_ = " + em.gen(n.a) + ";\n";
+                for (int j = 0; j < prog.kdim; ++j)
+                    src += "          part[" + std::to_string(n.red + j) + "] += t_ * kb[" +
+                           std::to_string(n.arg * FUSE_MAX_K + j) + "];\n";
+                src += "        }\n";
+            } else {
+                std::string term = n.op == FUSE_OP_DOT ? "(" + em.gen(n.a) + " * " + em.gen(n.b) + ")" : em.gen(n.a);
+                src += "        part[" + std::to_string(n.red) + "] += " + term + ";\n";
+            }
         }
         src += "    }\n";
-        begin = prog.red_end[s];
     }
     src += "}\n";
     const int root = prog.roots[0];
-    src += "#define FUSE_KRES " + std::to_string(prog.roots.size()) + "\n";
+    // row-vector results (k of them for a multi-aggregate), or row (x) k-vector: k values per element
     src += "__device__ __forceinline__ void fuse_final_elems(double a, const double *sv, const double *rsc,\n"
-           "                                                 const double *red, double *r)\n{\n";
-    for (size_t j = 0; j < prog.roots.size(); ++j)
-        src += "    r[" + std::to_string(j) + "] = " +
-               (prog.result_vec ? em.gen(prog.roots[j]) : std::string("0.0")) + ";\n";
+           "                                                 const double *kv, const double *red, double *r)\n{\n";
+    if (prog.result_kind == KIND_VK) {
+        const Node &n = prog.nodes[root];
+        src += "    const double t_ = " + em.gen(n.a) + ";\n";
+        for (int j = 0; j < kd; ++j)
+            src += "    r[" + std::to_string(j) + "] = t_ * " + em.gen(n.b, j) + ";\n";
+    } else {
+        for (int j = 0; j < kres; ++j)
+            src += "    r[" + std::to_string(j) + "] = " +
+                   (prog.result_kind == KIND_V ? em.gen(prog.roots[j]) : std::string("0.0")) + ";\n";
+    }
     src += "}\n";
     src += "__device__ __forceinline__ double fuse_final_elem(double a, const double *sv, const double *rsc,\n"
-           "                                                  const double *red)\n{\n    return " +
-           (prog.result_vec ? em.gen(root) : std::string("0.0")) + ";\n}\n";
-    src += "__device__ __forceinline__ double fuse_final_scalar(const double *rsc, const double *red)\n{\n"
-           "    return " + (prog.result_vec ? std::string("0.0") : em.gen(root)) + ";\n}\n";
+           "                                                  const double *kv, const double *red)\n{\n    return " +
+           (prog.result_kind == KIND_V ? em.gen(root) : std::string("0.0")) + ";\n}\n";
+    src += "__device__ __forceinline__ double fuse_final_scalar(const double *rsc, const double *kv,\n"
+           "                                                    const double *red)\n{\n    return " +
+           (prog.result_kind == KIND_S ? em.gen(root) : std::string("0.0")) + ";\n}\n";
+    src += "__device__ __forceinline__ void fuse_final_kvec(const double *rsc, const double *kv, const double *red,\n"
+           "                                                double *r)\n{\n";
+    for (int j = 0; j < kd; ++j)
+        src += "    r[" + std::to_string(j) + "] = " +
+               (prog.result_kind == KIND_K ? em.gen(root, j) : std::string("0.0")) + ";\n";
+    src += "}\n";
     return src;
 }
 

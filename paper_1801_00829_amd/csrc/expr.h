@@ -13,30 +13,41 @@ namespace fuse {
 
 enum class Tmpl { CELL, ROW_DENSE, ROW_CSR, OUTER };
 
+// Kinds of values in a body.  Cell / Outer bodies only have scalars (per cell /
+// per non-zero).  Row bodies: per-row scalar, row vector (n), per-row k-vector
+// (result of a product with an n x k right-hand side, or a KVEC side), the
+// right-hand side itself, and row (x) k-vector (n x k per row; result only).
+enum Kind { KIND_S = 0, KIND_V = 1, KIND_K = 2, KIND_M = 3, KIND_VK = 4 };
+
 struct Node {
     int op = 0;
     int arg = 0;
     double imm = 0.0;
     int a = -1, b = -1;      // operand node ids
-    bool vec = false;        // Row: row vector (true) or per-row scalar (false)
-    int level = 0;           // number of reductions below this node
-    bool zp = false;         // vector is zero wherever the main input has no stored cell
-    int red = -1;            // reduction number (ROWSUM / DOT nodes)
+    int kind = KIND_S;
+    bool vec = false;        // kind == KIND_V
+    int level = 0;           // number of cross-lane reductions below this node
+    bool zp = false;         // row vector is zero wherever the main input has no stored cell
+    int red = -1;            // first reduction slot (ROWSUM / DOT over columns: 1 slot; MATMULT: k slots)
 };
 
 struct Program {
     std::vector<Node> nodes;
     std::vector<int> roots;          // one per expression (MAgg: k)
-    std::vector<int> reductions;     // node ids ordered by stage
-    std::vector<int> red_end;        // red_end[s] = number of reductions in stages <= s
+    std::vector<int> reductions;     // node ids of cross-lane reductions, ordered by stage
+    std::vector<int> red_end;        // red_end[s] = number of reduction SLOTS in stages <= s
+    int nred = 0;                    // total number of reduction slots
     int nstage = 0;
-    bool result_vec = false;         // Row: kind of the (single) root
+    bool result_vec = false;         // Row: the result is a row vector
+    int result_kind = KIND_S;        // Row: kind of the (first) root
+    int kdim = 0;                    // length of k-vectors (0: none in this body)
     bool side_used[8] = {false, false, false, false, false, false, false, false};
 };
 
 // Parse and type-check `k` postfix expressions for a template.  side kinds
-// decide whether a SIDE token is a vector or a scalar in a Row body.  Returns
-// FUSE_OK or FUSE_EDESC / FUSE_EINVAL with a message in err.
+// decide the kind of a SIDE token in a Row body.  Equal sub-expressions become
+// one node (a row aggregate that occurs twice is computed once).  Returns
+// FUSE_OK or FUSE_EDESC / FUSE_EINVAL / FUSE_EUNSUPPORTED with a message in err.
 int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides, int nsides,
                   Program &prog, std::string &err);
 
@@ -47,8 +58,9 @@ std::string program_key(const Program &prog);
 std::string emit_cell_body(const Program &prog);
 // Body source for the Outer skeleton: fuse_body(a, d, s) -> double.
 std::string emit_outer_body(const Program &prog);
-// Body source for the Row skeletons: stage functions, final element / scalar,
-// FUSE_NSTAGE, FUSE_NRED, fuse_red_end[], FUSE_RESULT_VEC.
+// Body source for the Row skeletons: stage functions, final element / scalar /
+// k-vector functions, FUSE_NSTAGE, FUSE_NRED, fuse_red_end[], FUSE_RESULT_KIND,
+// FUSE_KRES, FUSE_KMAX.
 std::string emit_row_body(const Program &prog);
 
 }  // namespace fuse

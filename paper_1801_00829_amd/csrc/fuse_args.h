@@ -5,6 +5,9 @@
 
 #define FUSE_MAX_SIDES 8
 #define FUSE_MAX_AGGS 16
+#ifndef FUSE_MAX_K
+#define FUSE_MAX_K 16
+#endif
 
 typedef struct {
     const double *x;                          /* dense main input, or CSR values      */

@@ -96,6 +96,20 @@ int check_sides(const fuse_side *sides, int nsides, int64_t m, int64_t n, bool n
             break;
         case FUSE_SIDE_SCALAR:
             break;
+        case FUSE_SIDE_RHS:
+            if (s.m.rows != n || s.m.cols < 1 || s.m.cols > FUSE_MAX_K)
+                return fail(FUSE_ESHAPE, at + "right-hand side must be " + std::to_string(n) + " x k, 1 <= k <= " +
+                                             std::to_string(FUSE_MAX_K));
+            if (s.m.ld < s.m.cols)
+                return fail(FUSE_ESHAPE, at + "ld < cols");
+            break;
+        case FUSE_SIDE_KVEC:
+            if (s.m.rows != m || s.m.cols < 1 || s.m.cols > FUSE_MAX_K)
+                return fail(FUSE_ESHAPE, at + "k-vector side must be " + std::to_string(m) + " x k, 1 <= k <= " +
+                                             std::to_string(FUSE_MAX_K));
+            if (s.m.ld < s.m.cols)
+                return fail(FUSE_ESHAPE, at + "ld < cols");
+            break;
         default:
             return fail(FUSE_EINVAL, at + "unknown side kind " + std::to_string(s.kind));
         }
@@ -210,8 +224,14 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     Runtime &rt = Runtime::get();
     const int64_t m = X->rows, n = X->cols;
     const int ac = agg_code(agg);
-    if (prog.result_vec ? false : (ac == 2 || ac == 3))
+    const int rk = prog.result_kind;
+    if (rk == KIND_S && (ac == 2 || ac == 3))
         return fail(FUSE_EDESC, "row / column aggregation needs a row-vector result");
+    if (rk == KIND_K && ac == 2)
+        return fail(FUSE_EDESC, "a k-vector result has the variants no_agg, col_agg and full_agg");
+    if (rk == KIND_VK && ac != 3)
+        return fail(FUSE_EDESC, "an OUTERK result needs FUSE_AGG_COL / FUSE_AGG_COL_T");
+    const int kd = prog.kdim;
 
     // vector width: 16-byte loads need even strides and aligned bases
     bool vec2 = (n % 2 == 0) && (X->ld % 2 == 0) && (!launch || aligned16(X->data));
@@ -228,7 +248,9 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     const int VEC = vec2 ? 2 : 1;
     const int64_t nvec = (n + VEC - 1) / VEC;
     // lanes per row and vectors per lane
-    const int epl_target = env_int("FUSE_ROW_EPL", 4);
+    int epl_target = env_int("FUSE_ROW_EPL", 4);
+    if (kd > 0)      // k values per owned column are kept in registers (right-hand side, accumulators)
+        epl_target = std::max(1, std::min(epl_target, 16 / (VEC * kd)));
     int G = 1;
     while (G < 64 && (nvec + G - 1) / G > epl_target)
         G <<= 1;
@@ -244,6 +266,9 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     if (epl64 < 1)
         epl64 = 1;
     const int EPL = (int)epl64;
+    if (kd > 0 && (stripes > 1 || EPL * VEC * kd > 48))
+        return fail(FUSE_EUNSUPPORTED, "Row bodies with k-vectors need ceil(cols / " + std::to_string(64 * VEC) +
+                                           ") * " + std::to_string(VEC) + " * k <= 48 in this build");
     int RS = env_int("FUSE_ROW_RS", 0);
     if (RS <= 0)
         RS = EPL >= 8 ? 1 : (EPL >= 3 ? 2 : 4);
@@ -277,7 +302,11 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     Plan::Loaded fn;
     if ((rc = rt.load(*plan, fn, g_err)))
         return rc;
-    const int64_t out_count = ac == 0 ? (prog.result_vec ? m * n : m) : ac == 1 ? 1 : ac == 2 ? m : n;
+    int64_t out_count = ac == 0 ? (prog.result_vec ? m * n : m) : ac == 1 ? 1 : ac == 2 ? m : n;
+    if (rk == KIND_K)
+        out_count = ac == 0 ? m * kd : ac == 3 ? kd : 1;
+    else if (rk == KIND_VK)
+        out_count = n * kd;
     if (m == 0 || n == 0)
         return zero_fill(fn, out, out_count, stream);
 
@@ -288,9 +317,12 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     const int64_t cap = std::max<int64_t>(1, (int64_t)cus * env_int("FUSE_ROW_BLOCKS_PER_CU", 2) / stripes);
     gx = std::min(gx, cap);
     Workspace ws;
+    const int64_t nacc = rk == KIND_VK ? kd : 1;      // running sums per column
     size_t need = 64;
-    if (ac == 3)
-        need = (size_t)gx * (size_t)n;
+    if (ac == 3 && rk == KIND_K)
+        need = (size_t)gx * (size_t)kd;
+    else if (ac == 3)
+        need = (size_t)gx * (size_t)(n * nacc);
     else if (ac == 1)
         need = (size_t)gx * stripes;
     else if (ac == 2 && stripes > 1)
@@ -310,8 +342,8 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     fill_side_args(A, sides, nsides);
     if ((rc = rt.launch(fn.main, (unsigned)gx, (unsigned)stripes, BLOCK, stream, &A, sizeof A, g_err)))
         return rc;
-    if (ac == 3)
-        return run_combine(fn, ws.partials, (int)gx, (int)n, out, stream);
+    if (ac == 3 && rk != KIND_K)
+        return run_combine(fn, ws.partials, (int)gx, (int)(n * nacc), out, stream);
     if (ac == 2 && stripes > 1)
         return run_combine(fn, ws.partials, stripes, (int)m, out, stream);
     return 0;
@@ -605,7 +637,7 @@ int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, co
     if (nsides < 0 || nsides > FUSE_MAX_SIDES || (nsides > 0 && !sides))
         return fail(FUSE_EINVAL, "bad sides / nsides");
     for (int q = 0; q < nsides; ++q)
-        if (sides[q].kind < 0 || sides[q].kind > 3)
+        if (sides[q].kind < 0 || sides[q].kind > FUSE_SIDE_KVEC)
             return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
     Program prog;
     if ((rc = parse_program(Xd ? Tmpl::ROW_DENSE : Tmpl::ROW_CSR, expr, 1, sides, nsides, prog, g_err)))
@@ -616,7 +648,11 @@ int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, co
     {
         const int ac = agg_code(agg);
         const int64_t cells = Xd ? m * n : Xs->nnz;
-        const int64_t count = ac == 1 ? 1 : ac == 2 ? m : ac == 3 ? n : (prog.result_vec ? cells : m);
+        int64_t count = ac == 1 ? 1 : ac == 2 ? m : ac == 3 ? n : (prog.result_vec ? cells : m);
+        if (prog.result_kind == KIND_K)
+            count = ac == 0 ? m * prog.kdim : ac == 3 ? prog.kdim : 1;
+        else if (prog.result_kind == KIND_VK)
+            count = n * prog.kdim;
         if (launch && !out && count > 0)
             return fail(FUSE_EINVAL, "out is NULL");
     }

@@ -511,3 +511,65 @@ def test_sparse_cell_paper_expression_and_rejections():
         with pytest.raises(F.FuseError) as e:
             F.fuse_cell_csr(bad, xd, sd, "full")
         assert e.value.code == -3
+
+
+# ------------------------------------------- Row with a matrix right-hand side ---
+
+MLOG_Q = [("side", 1), ("main",), ("side", 0), ("matmult",), ("mul",)]                   # Q = P * (X V)
+MLOGREG = [("main",)] + MLOG_Q + [("side", 1)] + MLOG_Q + [("rowsum",), ("mul",), ("sub",), ("outerk",)]
+TXXV = [("main",), ("main",), ("side", 0), ("matmult",), ("outerk",)]                     # t(X) (X V)
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (70, 10, 3), (333, 100, 4), (129, 101, 2), (64, 1000, 2), (50, 784, 1),
+                                   (500, 37, 16)])
+def test_row_matrix_rhs_chain_and_mlogreg_core(shape):
+    """t(X) %*% (X %*% V) with an n x k right-hand side (Fig. 8g) and the multinomial logistic
+    regression core H = t(X) (Q - P * rowSums(Q)), Q = P * (X V)  (Sec. 2.2, second example)."""
+    import paper_1801_00829_amd as F
+    from oracle import plans
+    m, n, k = shape
+    rng = np.random.default_rng(71)
+    x, v, p = rng.normal(size=(m, n)), rng.normal(size=(n, k)), rng.uniform(size=(m, k))
+    xd, vd, pd = to_dev(x), to_dev(v), to_dev(p)
+    sd = [("rhs", vd), ("kvec", pd)]
+    print("row matrix rhs", shape, flush=True)
+    absx, absv = np.abs(x), np.abs(v)
+    scale = max((absx.T @ (absx @ absv)).max(), 1e-300)
+    got = host(F.fuse_row(TXXV, xd, sd, "col_t")).reshape(n, k)
+    assert_close(got, plans.row_tx_xv_matrix(x, v), scale=scale, what="t(X)(XV)")
+    got = host(F.fuse_row(MLOGREG, xd, sd, "col_t")).reshape(n, k)
+    assert_close(got, plans.mlogreg_core(x, v, p), scale=2 * k * scale, what="mlogreg core")
+    assert_close(got, unfused.row_dense(MLOGREG, x, [("rhs", v), ("kvec", p)], "col_t"), scale=2 * k * scale,
+                 what="mlogreg core vs generic evaluator")
+    # k-vector results: X V (no_agg), its column sums, its total; rowSums(Q) per row
+    xv = [("main",), ("side", 0), ("matmult",)]
+    s1 = max((absx @ absv).max(), 1e-300)
+    assert_close(host(F.fuse_row(xv, xd, sd, "none")).reshape(m, k), x @ v, scale=s1, what="X V")
+    assert_close(host(F.fuse_row(xv, xd, sd, "col")), unfused.row_dense(xv, x, [("rhs", v)], "col"),
+                 scale=(absx @ absv).sum(0).max(), what="colSums(X V)")
+    assert_close(host(F.fuse_row(xv, xd, sd, "full")), unfused.row_dense(xv, x, [("rhs", v)], "full"),
+                 scale=(absx @ absv).sum(), what="sum(X V)")
+    assert_close(host(F.fuse_row(MLOG_Q + [("rowsum",)], xd, sd, "none")),
+                 unfused.row_dense(MLOG_Q + [("rowsum",)], x, [("rhs", v), ("kvec", p)], "none"),
+                 scale=(absx @ absv).sum(1).max(), what="rowSums(Q)")
+
+
+def test_row_matrix_rhs_strided_sides_and_limits():
+    import paper_1801_00829_amd as F
+    from oracle import plans
+    rng = np.random.default_rng(72)
+    m, n, k = 200, 50, 3
+    x = rng.normal(size=(m, n))
+    vb, pb = rng.normal(size=(n, k + 2)), rng.uniform(size=(m, k + 5))
+    v, p = vb[:, 1:1 + k], pb[:, 2:2 + k]
+    got = host(F.fuse_row(MLOGREG, to_dev(x), [("rhs", to_dev(vb)[:, 1:1 + k]), ("kvec", to_dev(pb)[:, 2:2 + k])],
+                          "col_t")).reshape(n, k)
+    assert_close(got, plans.mlogreg_core(x, v, p), scale=np.abs(x).T @ (np.abs(x) @ np.abs(v)) * 2 * k, what="strided rhs")
+    import torch
+    with pytest.raises(F.FuseError) as e:       # too many columns for the register-resident form
+        F.fuse_row(TXXV, torch.ones((4, 2000), dtype=torch.float64, device="cuda"),
+                   [("rhs", torch.ones((2000, 8), dtype=torch.float64, device="cuda"))], "col_t")
+    assert e.value.code == -7
+    with pytest.raises(F.FuseError) as e:       # shapes: the right-hand side must have cols(X) rows
+        F.fuse_row(TXXV, to_dev(x), [("rhs", to_dev(np.ones((n + 1, k))))], "col_t")
+    assert e.value.code == -2
