@@ -178,6 +178,41 @@ def test_row_type_checking_and_sparse_safety(F):
     assert e.value.code == -7
 
 
+def test_row_matrix_rhs_type_checking(F):
+    """vectMatMult / vectOuterMultAdd bodies (Sec. 4.2 Row template; Fig. 8g): kinds, shapes, limits."""
+    xv = [("main",), ("side", 0), ("matmult",)]                           # X V  -> one k-vector per row
+    F.prepare_row(xv, (1000, 100), [("rhs", (100, 4))], "none")            # m x k output
+    assert "#define FUSE_KDIM 4" in F.last_source()
+    F.prepare_row(xv, (1000, 100), [("rhs", (100, 4))], "col")             # k column sums
+    txxv = [("main",)] + xv + [("outerk",)]                               # t(X) (X V): n x k
+    F.prepare_row(txxv, (1000, 100), [("rhs", (100, 4))], "col_t")
+    # equal sub-expressions are emitted once: Q = P * (X V) is used twice in the MLogreg core
+    q = xv + [("side", 1), ("mul",)]
+    core = [("main",)] + q + q + [("rowsum",), ("side", 1), ("mul",), ("sub",), ("outerk",)]
+    F.prepare_row(core, (1000, 100), [("rhs", (100, 4)), ("kvec", (1000, 4))], "col_t")
+    assert "#define FUSE_NRED 4" in F.last_source()                       # one X V product, not two
+    bad = [
+        (xv, [("rhs", (99, 4))], "none", -2),                            # V needs n rows
+        (xv, [("rhs", (100, 17))], "none", -3),                           # k beyond FUSE_MAX_K
+        (xv + [("side", 1), ("mul",)], [("rhs", (100, 4)), ("kvec", (1000, 3))], "none", -3),   # k mismatch
+        (xv + [("side", 1), ("mul",)], [("rhs", (100, 4)), ("kvec", (999, 4))], "none", -2),    # kvec rows
+        (txxv, [("rhs", (100, 4))], "none", -3),                          # n x k values only as column aggregate
+        ([("main",), ("side", 0), ("outerk",)], [("rowvec", None)], "col_t", -3),   # outerk needs a k-vector
+        ([("side", 0), ("main",), ("matmult",)], [("rhs", (100, 4))], "none", -3),  # operand order
+        (xv, [("rhs", (100, 4))], "row", -3),                             # rowSums of a k-vector: use ROWSUM
+    ]
+    for expr, sides, agg, code in bad:
+        with pytest.raises(F.FuseError) as e:
+            F.prepare_row(expr, (1000, 100), sides, agg)
+        assert e.value.code == code, (expr, sides, agg, e.value.code, str(e.value))
+    with pytest.raises(F.FuseError) as e:                                 # register budget: ceil(n/128)*2*k <= 48
+        F.prepare_row(txxv, (100, 2000), [("rhs", (2000, 4))], "col_t")
+    assert e.value.code == -7
+    with pytest.raises(F.FuseError) as e:                                 # CSR main input
+        F.prepare_row(xv, (1000, 100), [("rhs", (100, 4))], "none", nnz=500)
+    assert e.value.code in (-3, -7)
+
+
 def test_every_operator_compiles(F):
     un = ["neg", "abs", "sqrt", "exp", "log", "pow2", "sign", "neq0", "sigmoid"]
     bi = ["add", "sub", "mul", "div", "min", "max", "pow", "lt", "le", "gt", "ge", "eq", "ne"]
