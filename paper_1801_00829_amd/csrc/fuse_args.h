@@ -23,6 +23,10 @@ typedef struct {
     double *partials;                         /* workspace: per-block partial sums    */
     unsigned int *ticket;                     /* workspace: zeroed arrival counter    */
     int rank;                                 /* Outer: columns of U and V            */
+    int npanels;                              /* Outer: column panels of V (0: none)  */
+    void *panel_ptr;                          /* Outer workspace: per panel and row, the first stored cell at or
+                                                 after the panel's first column ((npanels+1) x m offsets)         */
+    int panel_w;                              /* Outer: columns per panel             */
     int pad_;
 } fuse_kargs;
 

@@ -742,8 +742,41 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     for (int q = 0; q < nsides; ++q)
         need_col |= prog.side_used[q] && (sides[q].kind == FUSE_SIDE_MATRIX || sides[q].kind == FUSE_SIDE_ROWVEC);
 
+    // Column panels of V: worth it when V overflows an L2 and a row still has a few cells per panel.
+    // Measured on 1e5 x 1e5, 100 cells per row, rank 100 (V = 80 MB): 8 to 16 panels are best; more
+    // panels raise the L2 hit rate of the V gathers but stream U once more per panel.
+    // FUSE_OUTER_PANELS: 0 never, 1 by this heuristic, 2 always (tests: panels on small inputs).
+    int npanels = 0, panel_w = 0;
+    const int panel_mode = env_int("FUSE_OUTER_PANELS", 1);
+    if (mode <= 1 && panel_mode != 0 && X->rows > 0 && X->cols > 0) {
+        const bool force = panel_mode == 2;
+        const int64_t vbytes = X->cols * V->ld * 8;
+        const int64_t panel_bytes = (int64_t)std::max(1, env_int("FUSE_OUTER_PANEL_KB", 5120)) * 1024;
+        if (force || vbytes > (int64_t)env_int("FUSE_OUTER_PANEL_MIN_KB", 4096) * 1024) {
+            int64_t P = (vbytes + panel_bytes - 1) / panel_bytes;
+            P = std::min<int64_t>((P + 7) / 8 * 8, 1024);
+            const double per_row = (double)X->nnz / (double)X->rows;
+            while (!force && P > 8 && per_row / (double)P < 2.0)
+                P -= 8;
+            const int64_t W = std::max<int64_t>(1, (X->cols + P - 1) / P);
+            P = (X->cols + W - 1) / W;
+            const int64_t pp_bytes = (P + 1) * X->rows * (X->rowptr_is64 ? 8 : 4);
+            if ((force || per_row / (double)P >= 1.0) && P >= 2 && pp_bytes <= ((int64_t)1 << 30)) {
+                npanels = (int)P;
+                panel_w = (int)W;
+            }
+        }
+    }
+    const bool panels = npanels > 0;
+    if (panels) {
+        UNR = env_int("FUSE_OUTER_PANEL_UNR", 2);
+        UNR = std::max(1, std::min(UNR, G));
+        while (G % UNR)
+            --UNR;
+    }
+
     const bool out_vec = vec2 && (!launch || aligned16(out));
-    const std::string key = std::string("outer|") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
+    const std::string key = std::string("outer|") + (panels ? "panels|" : "") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(mode) + (mode == 2 && out_vec ? "o" : "") + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
                             std::to_string(EPL) + "u" + std::to_string(UNR) + "b" + std::to_string(BLOCK) + "w" +
                             std::to_string(X->rowptr_is64 != 0);
@@ -757,7 +790,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
              "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_UNR " + std::to_string(UNR) +
              "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_MODE " +
              std::to_string(mode) + "\n#define FUSE_OUT_VEC " + std::to_string(out_vec) + "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) +
-             "\n#define FUSE_NEED_COL " + std::to_string(need_col) + "\n";
+             "\n#define FUSE_NEED_COL " + std::to_string(need_col) + "\n#define FUSE_PANELS " + std::to_string(panels) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_outer_body(prog);
         s += kSrcOuter;
@@ -781,8 +814,19 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     const int NW = BLOCK / 64;
     int64_t gx = (X->rows + NW - 1) / NW;
     gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_OUTER_BLOCKS_PER_CU", 8)));
+    size_t pp_doubles = 0;
+    if (panels) {
+        // every block must be resident from the start: blocks that start late walk the panels out of
+        // step with their XCD and evict the panel the others are using
+        int bpc = env_int("FUSE_OUTER_PANEL_BLOCKS_PER_CU", 0);
+        if (bpc <= 0)
+            bpc = rt.resident_blocks_per_cu(fn.main, BLOCK);
+        gx = std::max<int64_t>(8, (int64_t)cus * bpc / 8 * 8);
+        pp_doubles = (size_t)(npanels + 1) * (size_t)X->rows * (X->rowptr_is64 ? 8 : 4) / 8 + 1;
+    }
+    const size_t part_doubles = ((size_t)gx + 15) / 16 * 16;
     Workspace ws;
-    if ((rc = rt.workspace(stream, (size_t)gx, ws, g_err)))
+    if ((rc = rt.workspace(stream, part_doubles + pp_doubles, ws, g_err)))
         return rc;
     fuse_kargs A;
     std::memset(&A, 0, sizeof A);
@@ -801,6 +845,16 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     A.partials = ws.partials;
     A.ticket = ws.ticket;
     fill_side_args(A, sides, nsides);
+    if (panels) {
+        if (!fn.prep)
+            return fail(FUSE_ERUNTIME, "panel plan without its preparatory kernel");
+        A.npanels = npanels;
+        A.panel_w = panel_w;
+        A.panel_ptr = ws.partials + part_doubles;
+        const int64_t gp = (X->rows * 16 + 255) / 256;
+        if ((rc = rt.launch(fn.prep, (unsigned)gp, 1, 256, stream, &A, sizeof A, g_err)))
+            return rc;
+    }
     return rt.launch(fn.main, (unsigned)gx, 1, BLOCK, stream, &A, sizeof A, g_err);
 }
 

@@ -116,6 +116,9 @@ int Runtime::load(Plan &p, Plan::Loaded &fn, std::string &err)
         e = hipModuleGetFunction(&l.combine, l.module, "fuse_combine_cols");
     if (e == hipSuccess)
         e = hipModuleGetFunction(&l.fill, l.module, "fuse_fill");
+    if (e == hipSuccess && p.source.find("void __launch_bounds__(256) fuse_outer_prep") != std::string::npos &&
+        p.source.find("#define FUSE_PANELS 1") != std::string::npos)
+        e = hipModuleGetFunction(&l.prep, l.module, "fuse_outer_prep");
     if (e != hipSuccess) {
         err = std::string("hipModuleGetFunction: ") + hipGetErrorString(e);
         (void)hipModuleUnload(l.module);
@@ -161,6 +164,22 @@ int Runtime::workspace(hipStream_t stream, size_t doubles, Workspace &ws, std::s
     }
     ws = w;
     return 0;
+}
+
+int Runtime::resident_blocks_per_cu(hipFunction_t f, int block)
+{
+    std::lock_guard<std::mutex> lk(mu_);
+    auto key = std::make_pair(f, block);
+    auto it = resident_.find(key);
+    if (it != resident_.end())
+        return it->second;
+    int nb = 0;
+    if (hipModuleOccupancyMaxActiveBlocksPerMultiprocessor(&nb, f, block, 0) != hipSuccess || nb < 1) {
+        (void)hipGetLastError();
+        nb = 1;
+    }
+    resident_[key] = nb;
+    return nb;
 }
 
 int Runtime::launch(hipFunction_t f, unsigned gx, unsigned gy, unsigned block, hipStream_t stream,
@@ -211,6 +230,7 @@ void Runtime::clear()
             if (d.second.module)
                 (void)hipModuleUnload(d.second.module);
     plans_.clear();
+    resident_.clear();
     for (auto &kv : ws_) {
         if (kv.second.partials)
             (void)hipFree(kv.second.partials);

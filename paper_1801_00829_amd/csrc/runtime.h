@@ -25,6 +25,7 @@ struct Plan {
         hipFunction_t main = nullptr;
         hipFunction_t combine = nullptr;    // fuse_combine_cols
         hipFunction_t fill = nullptr;       // fuse_fill
+        hipFunction_t prep = nullptr;       // fuse_outer_prep (Outer plans with column panels only)
     };
     std::map<int, Loaded> per_device;
 };
@@ -72,6 +73,8 @@ public:
     int load(Plan &p, Plan::Loaded &fn, std::string &err);
     // Workspace of (current device, stream) with room for `doubles` partials.
     int workspace(hipStream_t stream, size_t doubles, Workspace &ws, std::string &err);
+    // Workgroups of `block` threads of kernel `f` that one compute unit holds at once (>= 1).
+    int resident_blocks_per_cu(hipFunction_t f, int block);
     int launch(hipFunction_t f, unsigned gx, unsigned gy, unsigned block, hipStream_t stream,
                const void *args, size_t arg_bytes, std::string &err);
 
@@ -90,6 +93,7 @@ private:
     std::map<std::pair<int, hipStream_t>, Workspace> ws_;
     std::vector<void *> retired_;
     std::map<int, int> cus_;
+    std::map<std::pair<hipFunction_t, int>, int> resident_;
     std::string arch_;
     int64_t hits_ = 0, misses_ = 0;
     double compile_ms_ = 0.0;

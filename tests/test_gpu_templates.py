@@ -298,8 +298,20 @@ def test_row_csr_rejects_programs_that_are_not_sparse_safe():
 
 # ------------------------------------------------------------------------ Outer ---
 
+@pytest.fixture(params=["rows", "panels"])
+def outer_mapping(request, monkeypatch):
+    """Both mappings of the no_agg / full_agg Outer skeleton: a wave per row, or column panels of V
+    (forced here with tiny panels; by default only chosen when V overflows an L2)."""
+    if request.param == "panels":
+        monkeypatch.setenv("FUSE_OUTER_PANELS", "2")
+        monkeypatch.setenv("FUSE_OUTER_PANEL_KB", "1")
+    else:
+        monkeypatch.setenv("FUSE_OUTER_PANELS", "0")
+    return request.param
+
+
 @pytest.mark.parametrize("case", range(12))
-def test_outer_random_expressions(case):
+def test_outer_random_expressions(case, outer_mapping):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(9000 + case)
     m, n, r = [(1, 1, 1), (30, 20, 7), (200, 300, 100), (64, 64, 20), (500, 100, 33), (40, 2000, 128)][case % 6]
@@ -320,7 +332,7 @@ def test_outer_random_expressions(case):
         assert_close(got, ref, scale=scale, tol=1e-9 if agg == "full" else 1e-10, what="outer %s" % agg)
 
 
-def test_outer_closed_forms_patterns_and_index_exactness():
+def test_outer_closed_forms_patterns_and_index_exactness(outer_mapping):
     import math
     import paper_1801_00829_amd as F
     body = [("main",), ("uvdot",), ("const", 1e-15), ("add",), ("log",), ("mul",)]
@@ -340,6 +352,8 @@ def test_outer_closed_forms_patterns_and_index_exactness():
             assert np.array_equal(got, (rows + 1.0) * (ci + 1.0))
             # number of processed stored cells == rowptr[m]
             assert host(F.fuse_outer([("main",), ("neq0",)], xd, to_dev(u2), to_dev(v2), [], "full"))[0] == float(rp[-1])
+            if n > 1 and va.size:
+                assert ("#define FUSE_PANELS 1" in F.last_source()) == (outer_mapping == "panels")
     # zero rows of U: every stored cell of those rows contributes x * log(1e-15)
     rp, ci, va = W.csr_bernoulli(60, 50, 0.2, 11)
     u = np.ones((60, 100))
@@ -350,7 +364,7 @@ def test_outer_closed_forms_patterns_and_index_exactness():
     assert_close(got, plans.outer_sum_x_log_uv(x, u, np.ones((50, 100))), what="outer zero rows")
 
 
-def test_outer_rowptr64_and_strided_factors():
+def test_outer_rowptr64_and_strided_factors(outer_mapping):
     import paper_1801_00829_amd as F
     from oracle import plans
     rng = np.random.default_rng(12)
