@@ -32,6 +32,9 @@ const char *kSrcRowDense =
 const char *kSrcRowCsr =
 #include "skel_row_csr.inc"
     ;
+const char *kSrcRowCsrStream =
+#include "skel_row_csr_stream.inc"
+    ;
 const char *kSrcOuter =
 #include "skel_outer.inc"
     ;
@@ -494,6 +497,14 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     }
     const int RS = std::max(1, env_int("FUSE_CSR_RS", 1));
     const int BLOCK = std::max(64, env_int("FUSE_CSR_BLOCK", 1024));
+    // Short rows (a lane group per row would cover <= 32 cells): the streaming skeleton, where a
+    // wave reads runs of whole rows as contiguous cells.  FUSE_CSR_STREAM: 0 never, 1 always, 2 by this rule.
+    const int stream_mode = env_int("FUSE_CSR_STREAM", 2);
+    const bool streaming = stream_mode == 1 || (stream_mode == 2 && G * C <= 32);
+    const int SC = 4;                                    // cells per lane of the streaming skeleton
+    bool need_rid = prog.nred > 0 || ac == 2 || !prog.result_vec;
+    for (int k = 0; k < nsides; ++k)
+        need_rid |= prog.side_used[k] && (sides[k].kind == FUSE_SIDE_MATRIX || sides[k].kind == FUSE_SIDE_COLVEC);
 
     // LDS plan: the column accumulator first, then staged row-vector sides if they fit
     int nrv = 0;
@@ -506,21 +517,23 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     const bool stage_rv = nrv > 0 && ((ac == 3 ? n : 0) + (int64_t)nrv * n) * 8 <= lds_budget - 1024;
     const int64_t npad = (ac == 3 || stage_rv) ? std::max<int64_t>(n, 1) : 1;
 
+    const int nt = env_int("FUSE_CSR_NT", streaming ? 1 : 0);
     const std::string key = std::string("rowcsr|") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
-                            std::to_string(ac) + "|g" + std::to_string(G) + "c" + std::to_string(C) + "r" + std::to_string(RS) + "b" +
+                            std::to_string(ac) + (streaming ? "|stream" + std::to_string(SC) + "r" + std::to_string(need_rid)
+                                                            : "|g" + std::to_string(G) + "c" + std::to_string(C) + "r" + std::to_string(RS)) + "b" +
                             std::to_string(BLOCK) + "p" + std::to_string(npad) + "s" + std::to_string(stage_rv) +
                             "w" + std::to_string(X->rowptr_is64 != 0) + std::to_string(m < (1LL << 30)) + "nt" +
-                            std::to_string(env_int("FUSE_CSR_NT", 0));
+                            std::to_string(nt);
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, name_prefix, [&](const std::string &name) {
         std::string s = kSrcArgs;
-        // plain (cached) loads: the register slots of neighbouring rows overlap in
-        // memory, so lines are re-used from cache rather than streamed once
-        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_CSR_NT", 0)) + "\n";
+        // group form: plain (cached) loads, the register slots of neighbouring rows overlap in
+        // memory, so lines are re-used from cache; streaming form: every cell is read once
+        s += "#define FUSE_NT " + std::to_string(nt) + "\n";
         s += kSrcCommon;
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
-        s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_C " + std::to_string(C) +
-             "\n#define FUSE_RS " + std::to_string(RS) +
+        s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_C " + std::to_string(streaming ? SC : C) +
+             "\n#define FUSE_RS " + std::to_string(RS) + "\n#define FUSE_NEED_RID " + std::to_string(need_rid) +
              "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_AGG " + std::to_string(ac) +
              "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) + "\n#define FUSE_ROW32 " +
              std::to_string(m < (1LL << 30)) + "\n#define FUSE_NPAD " +
@@ -528,7 +541,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
              "\n#define FUSE_NRV " + std::to_string(std::max(nrv, 1)) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_row_body(prog);
-        s += kSrcRowCsr;
+        s += streaming ? kSrcRowCsrStream : kSrcRowCsr;
         g_last_source = s;
         return s;
     }, plan, g_err);
@@ -548,7 +561,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
 
     const int cus = rt.num_cus();
     const int NW = BLOCK / 64;
-    const int64_t rows_per_iter = (int64_t)(64 / G) * RS * NW;
+    const int64_t rows_per_iter = streaming ? NW : (int64_t)(64 / G) * RS * NW;
     int64_t gx = (m + rows_per_iter - 1) / rows_per_iter;
     gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CSR_BLOCKS_PER_CU", 1)));
     Workspace ws;

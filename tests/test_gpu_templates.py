@@ -223,8 +223,16 @@ def _csr_cases():
     yield "many_empty_rows", (rp2, ci[keep], va[keep]), (200, 64)
 
 
+@pytest.fixture(params=["groups", "stream"])
+def csr_mapping(request, monkeypatch):
+    """Both CSR Row skeletons: a lane group per row, or waves streaming runs of whole rows
+    (by default chosen from the mean row length)."""
+    monkeypatch.setenv("FUSE_CSR_STREAM", "1" if request.param == "stream" else "0")
+    return request.param
+
+
 @pytest.mark.parametrize("rowptr64", [False, True])
-def test_row_csr_workload_expression_on_all_patterns(rowptr64):
+def test_row_csr_workload_expression_on_all_patterns(rowptr64, csr_mapping):
     import paper_1801_00829_amd as F
     from oracle import plans
     expr = [("main",), ("side", 0), ("dot",), ("main",), ("mul",)]
@@ -239,7 +247,7 @@ def test_row_csr_workload_expression_on_all_patterns(rowptr64):
         assert_close(got, ref, scale=scale, what="row csr " + name)
 
 
-def test_row_csr_index_handling_is_bit_exact():
+def test_row_csr_index_handling_is_bit_exact(csr_mapping):
     """Counts and positions: with X = 1 on its pattern, row / column / full sums of
     the body `X` are integer counts; the no-agg output must sit at the exact positions."""
     import paper_1801_00829_amd as F
@@ -260,7 +268,7 @@ def test_row_csr_index_handling_is_bit_exact():
 
 
 @pytest.mark.parametrize("case", range(12))
-def test_row_csr_random_sparse_safe_expressions(case):
+def test_row_csr_random_sparse_safe_expressions(case, csr_mapping):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(8000 + case)
     m, n = [(1, 1), (37, 19), (300, 257), (64, 1000), (513, 40), (100, 3000)][case % 6]
@@ -478,7 +486,7 @@ def test_row_long_chain_expression(nops):
 # ------------------------------------------------- Cell / MAgg over a sparse X ---
 
 @pytest.mark.parametrize("case", range(10))
-def test_sparse_cell_and_magg_random_expressions(case):
+def test_sparse_cell_and_magg_random_expressions(case, csr_mapping):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(9700 + case)
     m, n = [(1, 1), (37, 19), (300, 1000), (1000, 100), (64, 3000)][case % 5]
@@ -505,7 +513,7 @@ def test_sparse_cell_and_magg_random_expressions(case):
         assert_close(got[j], one[0], scale=max(a.sum(), 1e-300), tol=1e-13, what="sparse magg vs cell [%d]" % j)
 
 
-def test_sparse_cell_paper_expression_and_rejections():
+def test_sparse_cell_paper_expression_and_rejections(csr_mapping):
     """sum(X * Y * Z) with a sparse X (density 0.1) and dense Y, Z: equals the dense operator
     on the densified X; bodies that are not sparse-safe are rejected."""
     import paper_1801_00829_amd as F
