@@ -25,8 +25,8 @@ ALL = ("cell", "magg", "row_dense", "row_csr", "outer")
 # workload sizes in this launch configuration, scaled by what the same counters read for
 # the 1 GiB copy probe (x2.000 for FETCH_SIZE, x1.000 for WRITE_SIZE); the summary is
 # profiles/bench_all_templates_hbm_traffic.txt.  Reported as roofline.traffic.
-MEASURED_TRAFFIC_BYTES = {"cell": 24.07e6, "magg": 2400.13e6, "row_dense": 809.00e6,
-                          "row_csr": 1372.38e6, "outer": 8739.78e6}
+MEASURED_TRAFFIC_BYTES = {"cell": 24.07e6, "magg": 2400.13e6, "row_dense": 808.90e6,
+                          "row_csr": 1381.12e6, "outer": 4840.83e6}
 
 
 def seconds_at(nbytes, gbps_):
@@ -201,7 +201,10 @@ def main():
             "seed": W.BASE_SEED},
         "roofline": {"bound": "hbm", "kernel": d["kernel"], "template": dominant, "achieved": d["GBps"],
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(d["GBps"] / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant)},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant),
+                     "traffic_GBps": round(gbps(MEASURED_TRAFFIC_BYTES.get(dominant), d["avg_us"] * 1e-6), 1),
+                     "note": ("Outer: algorithmic bytes by the gather model (one V row per non-zero); frac > 1 means "
+                              "gathers served by L2 (column panels), see traffic") if dominant == "outer" else ""},
         "templates": templates,
         "plan_cache": {"hits": hits, "misses": misses, "compile_ms": round(compile_ms, 1)},
     }
