@@ -225,7 +225,11 @@ int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
  *   agg LEFT_MM  : out is cols(X) x r, contiguous: out[j,:] = sum over the stored
  *                  cells (i, j) of column j of body * U[i,:]  (the mirrored variant;
  *                  accumulated with fp64 atomics: the order of additions is not fixed)
- * 1 <= r <= 1024. */
+ * 1 <= r <= 1024.  When V is larger than a few MB, FULL and NONE first build a table of
+ * per-row offsets into column panels in the library's workspace (one more kernel on
+ * the same stream; (P+1) x rows(X) offsets, P <= 1024 panels) and rely on the
+ * ascending column indices the CSR format prescribes; with other column orders the
+ * result is undefined (but no access leaves the arrays). */
 int fuse_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
                const fuse_side *sides, int nsides, int agg, double *out, void *stream);
 
