@@ -38,7 +38,7 @@ int fail(std::string &err, const std::string &msg)
 }  // namespace
 
 int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides, int nsides,
-                  Program &prog, std::string &err)
+                  Program &prog, std::string &err, bool cell_body)
 {
     const bool row = (t == Tmpl::ROW_DENSE || t == Tmpl::ROW_CSR);
     prog = Program();
@@ -210,17 +210,18 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
     }
     if (row) {
         const Node &r = prog.nodes[prog.roots[0]];
-        prog.result_vec = r.kind == KIND_V;
-        prog.result_kind = r.kind;
+        const int rkind = (cell_body && r.kind == KIND_S) ? KIND_V : r.kind;
+        prog.result_vec = rkind == KIND_V;
+        prog.result_kind = rkind;
         for (int root : prog.roots) {
             const Node &q = prog.nodes[root];
-            if (q.kind != r.kind)
+            if (((cell_body && q.kind == KIND_S) ? KIND_V : q.kind) != rkind)
                 return fail(err, "the results of a multi-aggregate must all be of the same kind");
             if (t == Tmpl::ROW_CSR && q.kind == KIND_V && !q.zp)
                 return fail(err, "not sparse-safe: the result is not zero where the main input has no "
                                  "stored cell");
         }
-        if (prog.roots.size() > 1 && r.kind != KIND_V)
+        if (prog.roots.size() > 1 && rkind != KIND_V)
             return fail(err, "several results need row-vector bodies");
         // order the cross-lane reductions by stage (= level of the reduction node - 1)
         auto is_red = [&](const Node &n) {

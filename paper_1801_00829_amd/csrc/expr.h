@@ -48,8 +48,11 @@ struct Program {
 // decide the kind of a SIDE token in a Row body.  Equal sub-expressions become
 // one node (a row aggregate that occurs twice is computed once).  Returns
 // FUSE_OK or FUSE_EDESC / FUSE_EINVAL / FUSE_EUNSUPPORTED with a message in err.
+// cell_body (Row templates): the expressions are Cell bodies evaluated per cell of the row, so a
+// result without any row-vector operand (only scalars / column-vector sides) still counts as a row
+// vector: it is the same value at every cell of the row.
 int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides, int nsides,
-                  Program &prog, std::string &err);
+                  Program &prog, std::string &err, bool cell_body = false);
 
 // Canonical text of a program (cache key part).
 std::string program_key(const Program &prog);

@@ -277,7 +277,7 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         RS = EPL >= 8 ? 1 : (EPL >= 3 ? 2 : 4);
     const int BLOCK = 256;
 
-    const std::string key = std::string("rowdense|") + pkey + "|" + side_key(sides, nsides) + "|agg" +
+    const std::string key = std::string("rowdense|") + pkey + "|rk" + std::to_string(rk) + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(ac) + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
                             std::to_string(EPL) + "r" + std::to_string(RS) + "nt" +
                             std::to_string(env_int("FUSE_NT", 1));
@@ -305,7 +305,10 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     Plan::Loaded fn;
     if ((rc = rt.load(*plan, fn, g_err)))
         return rc;
-    int64_t out_count = ac == 0 ? (prog.result_vec ? m * n : m) : ac == 1 ? 1 : ac == 2 ? m : n;
+    const int64_t nroots = (int64_t)prog.roots.size();          // > 1: MAgg bodies, full aggregate only
+    if (nroots > 1 && (ac != 1 || rk != KIND_V))
+        return fail(FUSE_EDESC, "several results only as full aggregates of row-vector bodies");
+    int64_t out_count = ac == 0 ? (prog.result_vec ? m * n : m) : ac == 1 ? nroots : ac == 2 ? m : n;
     if (rk == KIND_K)
         out_count = ac == 0 ? m * kd : ac == 3 ? kd : 1;
     else if (rk == KIND_VK)
@@ -327,7 +330,7 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     else if (ac == 3)
         need = (size_t)gx * (size_t)(n * nacc);
     else if (ac == 1)
-        need = (size_t)gx * stripes;
+        need = (size_t)gx * stripes * (size_t)nroots;
     else if (ac == 2 && stripes > 1)
         need = (size_t)stripes * (size_t)m;
     if ((rc = rt.workspace(stream, need, ws, g_err)))
@@ -397,14 +400,12 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
                 flat = false;
         }
     if (!flat) {
-        if (is_magg)
-            return fail(FUSE_EUNSUPPORTED, "MAgg needs contiguous matrices (ld == cols) and only matrix / "
-                                           "scalar side inputs in this build");
+        // 2-D form: the Cell body (or the k bodies of a MAgg) as a Row body without row aggregates
         Program rprog;
-        if ((rc = parse_program(Tmpl::ROW_DENSE, exprs, 1, sides, nsides, rprog, g_err)))
+        if ((rc = parse_program(Tmpl::ROW_DENSE, exprs, k, sides, nsides, rprog, g_err, true)))
             return rc;
         return row_dense_impl(rprog, program_key(rprog), X, sides, nsides, agg, out, stream, launch,
-                              "fuse_cell2d");
+                              is_magg ? "fuse_magg2d" : "fuse_cell2d");
     }
 
     bool vec2 = !launch || aligned16(X->data);

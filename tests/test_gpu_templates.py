@@ -146,6 +146,55 @@ def test_magg_random_and_equals_separate_cells(case):
         assert_close(got[j], one[0], scale=scale, tol=1e-13, what="magg vs cell [%d]" % j)
 
 
+@pytest.mark.parametrize("case", range(6))
+def test_magg_with_vector_sides_and_strided_inputs(case):
+    """MAgg bodies that need the 2-D form of the skeleton: row / column vector sides, views with a
+    leading dimension > cols.  Same bar as the flat form, and equal to the aggregates one by one."""
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(6100 + case)
+    m, n = [(1, 1), (19, 23), (300, 129), (64, 1024), (1001, 77), (7, 5000)][case]
+    k = int(rng.integers(1, 6))
+    pad = [0, 3, 2, 0, 5, 1][case]
+    xb, yb = rng.uniform(-1.5, 1.5, size=(m, n + pad)), rng.uniform(-1.5, 1.5, size=(m, n + pad))
+    x, y = xb[:, :n], yb[:, :n]
+    sides = [("matrix", y), ("colvec", rng.uniform(-1.5, 1.5, size=m)), ("rowvec", rng.uniform(-1.5, 1.5, size=n)),
+             ("scalar", np.array(0.7))]
+    exprs = [random_scalar_expr(rng, 4, depth=3) for _ in range(k)]
+    exprs[0] = [("main",), ("side", 1), ("mul",), ("side", 2), ("mul",)]         # uses both vector sides
+    print("magg 2-d case", case, (m, n), "pad", pad, exprs, flush=True)
+    xd = to_dev(xb)[:, :n]
+    sd = [("matrix", to_dev(yb)[:, :n]), ("colvec", to_dev(sides[1][1])), ("rowvec", to_dev(sides[2][1])),
+          ("scalar", 0.7)]
+    got = host(F.fuse_magg(exprs, xd, sd))
+    assert F.last_kernel().startswith("fuse_magg2d_")
+    ref = unfused.magg(exprs, x, sides)
+    for j in range(k):
+        scale = _abs_scale(unfused.cell(exprs[j], x, sides, "none"), "full", m, n)
+        assert_close(got[j], ref[j], scale=scale, what="magg2d[%d]" % j)
+        one = host(F.fuse_cell(exprs[j], xd, sd, "full"))
+        assert_close(got[j], one[0], scale=scale, tol=1e-13, what="magg2d vs cell [%d]" % j)
+
+
+def test_cell_bodies_without_a_matrix_operand():
+    """A Cell body made of scalars and a column vector only is still a value per CELL: no_agg
+    gives m x n values, the aggregates count every cell (2-D form of the skeleton)."""
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(77)
+    for (m, n) in ((1, 1), (5, 3), (70, 130), (300, 64)):
+        x = rng.uniform(size=(m, n))
+        cv = rng.uniform(1.0, 2.0, size=m)
+        sides = [("colvec", cv), ("scalar", np.array(1.5))]
+        sd = [("colvec", to_dev(cv)), ("scalar", 1.5)]
+        for expr in ([("side", 0)], [("side", 0), ("side", 1), ("mul",), ("const", 0.25), ("add",)]):
+            for agg in ("none", "row", "col", "full"):
+                print("cell no-matrix", (m, n), expr, agg, flush=True)
+                got = host(F.fuse_cell(expr, to_dev(x), sd, agg))
+                ref = unfused.cell(expr, x, sides, agg)
+                assert got.size == ref.size
+                assert_close(got.reshape(ref.shape), ref, scale=_abs_scale(unfused.cell(expr, x, sides, "none"), agg, m, n),
+                             what="cell no-matrix %s" % agg)
+
+
 # -------------------------------------------------------------------- Row dense ---
 
 ROW_SHAPES = [(1, 1), (5, 3), (70, 10), (33, 100), (129, 101), (40, 784), (17, 1000), (9, 2048), (300, 64)]
