@@ -34,8 +34,20 @@ def _check(rc):
         raise FuseError(rc, L.load().fuse_last_error().decode("utf-8", "replace"))
 
 
+_EXPR_CACHE = {}
+
+
 def _expr(tokens):
-    """Symbolic postfix list, e.g. [("main",), ("side", 0), ("mul",)] -> (Expr, keep-alive)."""
+    """Symbolic postfix list, e.g. [("main",), ("side", 0), ("mul",)] -> (Expr, keep-alive).
+    Marshalled descriptors are kept by value of the list, so a loop that issues the same
+    operator again does not rebuild the token array."""
+    try:
+        key = tuple(tuple(t) for t in tokens)
+        hit = _EXPR_CACHE.get(key)
+    except TypeError:                      # unhashable token entries: marshal without caching
+        key, hit = None, None
+    if hit is not None:
+        return hit
     arr = (L.Tok * max(len(tokens), 1))()
     for i, t in enumerate(tokens):
         name = t[0]
@@ -44,7 +56,12 @@ def _expr(tokens):
         arr[i].op = OPS[name]
         arr[i].arg = int(t[1]) if name == "side" else 0
         arr[i].imm = float(t[1]) if name == "const" else 0.0
-    return L.Expr(arr, len(tokens)), arr
+    res = (L.Expr(arr, len(tokens)), arr)
+    if key is not None:
+        if len(_EXPR_CACHE) > 1024:
+            _EXPR_CACHE.clear()
+        _EXPR_CACHE[key] = res
+    return res
 
 
 def _dense(t, rows=None, cols=None):

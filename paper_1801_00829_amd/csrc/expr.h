@@ -42,6 +42,7 @@ struct Program {
     int result_kind = KIND_S;        // Row: kind of the (first) root
     int kdim = 0;                    // length of k-vectors (0: none in this body)
     bool side_used[8] = {false, false, false, false, false, false, false, false};
+    std::string key;                 // canonical text (program_key), filled by parse_cached
 };
 
 // Parse and type-check `k` postfix expressions for a template.  side kinds

@@ -7,7 +7,9 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <string>
+#include <unordered_map>
 
 #include "expr.h"
 #include "runtime.h"
@@ -38,6 +40,69 @@ const char *kSrcRowCsrStream =
 const char *kSrcOuter =
 #include "skel_outer.inc"
     ;
+
+// Parsed descriptors by their raw bytes (template, tokens, side kinds): a call with a descriptor
+// seen before skips parsing, typing and the canonical key text -- the steady state of an operator
+// that is called in a loop (Sec. 2.1: "plan cache" lookups must be cheap next to a small operator).
+struct ParsedEntry {
+    int rc = 0;
+    std::string err;
+    Program prog;
+};
+std::mutex g_parse_mu;
+std::unordered_map<std::string, std::shared_ptr<const ParsedEntry>> g_parsed;
+
+int parse_cached(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides, int nsides, Program &prog,
+                 std::string &err, bool cell_body = false)
+{
+    std::string raw;
+    raw.reserve(256);
+    auto put = [&](const void *p, size_t n) { raw.append(static_cast<const char *>(p), n); };
+    const int head[4] = {(int)t, (int)cell_body, k, nsides};
+    put(head, sizeof head);
+    bool ok = exprs != nullptr && k >= 1 && k <= FUSE_MAX_AGGS && nsides >= 0 && nsides <= FUSE_MAX_SIDES &&
+              (nsides == 0 || sides != nullptr);
+    for (int x = 0; ok && x < k; ++x) {
+        if (!exprs[x].toks || exprs[x].ntoks < 0 || exprs[x].ntoks > 4096) {
+            ok = false;
+            break;
+        }
+        put(&exprs[x].ntoks, sizeof exprs[x].ntoks);
+        for (int q = 0; q < exprs[x].ntoks; ++q) {
+            const fuse_tok &tk = exprs[x].toks[q];
+            put(&tk.op, sizeof tk.op);
+            put(&tk.arg, sizeof tk.arg);
+            put(&tk.imm, sizeof tk.imm);
+        }
+    }
+    if (!ok)                                   // malformed: let the parser produce the message
+        return parse_program(t, exprs, k, sides, nsides, prog, err, cell_body);
+    for (int q = 0; q < nsides; ++q) {
+        const long long kc[2] = {sides[q].kind, (sides[q].kind == FUSE_SIDE_RHS || sides[q].kind == FUSE_SIDE_KVEC)
+                                                    ? (long long)sides[q].m.cols : 0};
+        put(kc, sizeof kc);
+    }
+    {
+        std::lock_guard<std::mutex> lk(g_parse_mu);
+        auto it = g_parsed.find(raw);
+        if (it != g_parsed.end()) {
+            prog = it->second->prog;
+            err = it->second->err;
+            return it->second->rc;
+        }
+    }
+    auto e = std::make_shared<ParsedEntry>();
+    e->rc = parse_program(t, exprs, k, sides, nsides, e->prog, e->err, cell_body);
+    if (e->rc == 0)
+        e->prog.key = program_key(e->prog);
+    prog = e->prog;
+    err = e->err;
+    std::lock_guard<std::mutex> lk(g_parse_mu);
+    if (g_parsed.size() > 4096)
+        g_parsed.clear();
+    g_parsed.emplace(std::move(raw), e);
+    return e->rc;
+}
 
 thread_local std::string g_err;
 thread_local std::string g_last_source;
@@ -383,7 +448,7 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
         for (int q = 0; q < nsides; ++q)
             if (sides[q].kind < 0 || sides[q].kind > 3)
                 return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
-        rc = parse_program(Tmpl::CELL, exprs, k, sides, nsides, prog, g_err);
+        rc = parse_cached(Tmpl::CELL, exprs, k, sides, nsides, prog, g_err);
         if (rc)
             return rc;
     }
@@ -402,9 +467,9 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
     if (!flat) {
         // 2-D form: the Cell body (or the k bodies of a MAgg) as a Row body without row aggregates
         Program rprog;
-        if ((rc = parse_program(Tmpl::ROW_DENSE, exprs, k, sides, nsides, rprog, g_err, true)))
+        if ((rc = parse_cached(Tmpl::ROW_DENSE, exprs, k, sides, nsides, rprog, g_err, true)))
             return rc;
-        return row_dense_impl(rprog, program_key(rprog), X, sides, nsides, agg, out, stream, launch,
+        return row_dense_impl(rprog, rprog.key, X, sides, nsides, agg, out, stream, launch,
                               is_magg ? "fuse_magg2d" : "fuse_cell2d");
     }
 
@@ -422,7 +487,7 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
     if (UNROLL <= 0)
         UNROLL = nmat <= 1 ? 8 : (nmat <= 4 ? 4 : 2);
 
-    const std::string key = std::string(is_magg ? "magg|" : "cell|") + program_key(prog) + "|" +
+    const std::string key = std::string(is_magg ? "magg|" : "cell|") + prog.key + "|" +
                             side_key(sides, nsides) + "|agg" + std::to_string(ac) + "|v" + std::to_string(VEC) +
                             "u" + std::to_string(UNROLL) + "nt" + std::to_string(env_int("FUSE_NT", 1));
     std::shared_ptr<Plan> plan;
@@ -522,7 +587,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     const int64_t npad = (ac == 3 || stage_rv) ? std::max<int64_t>(n, 1) : 1;
 
     const int nt = env_int("FUSE_CSR_NT", streaming ? 1 : 0);
-    const std::string key = std::string("rowcsr|") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
+    const std::string key = std::string("rowcsr|") + prog.key + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(ac) + (streaming ? "|stream" + std::to_string(SC) + "r" + std::to_string(need_rid)
                                                             : "|g" + std::to_string(G) + "c" + std::to_string(C) + "r" + std::to_string(RS)) + "b" +
                             std::to_string(BLOCK) + "p" + std::to_string(npad) + "s" + std::to_string(stage_rv) +
@@ -622,9 +687,9 @@ int cell_csr_impl(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
         if (sides[q].kind < 0 || sides[q].kind > 3)
             return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
     Program cprog, prog;
-    if ((rc = parse_program(Tmpl::CELL, exprs, k, sides, nsides, cprog, g_err)))     // Cell tokens only
+    if ((rc = parse_cached(Tmpl::CELL, exprs, k, sides, nsides, cprog, g_err)))     // Cell tokens only
         return rc;
-    if ((rc = parse_program(Tmpl::ROW_CSR, exprs, k, sides, nsides, prog, g_err)))   // kinds + sparse-safety
+    if ((rc = parse_cached(Tmpl::ROW_CSR, exprs, k, sides, nsides, prog, g_err)))   // kinds + sparse-safety
         return rc;
     if (!prog.result_vec)
         return fail(FUSE_EDESC, "not sparse-safe: the body does not depend on the main input");
@@ -657,7 +722,7 @@ int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, co
         if (sides[q].kind < 0 || sides[q].kind > FUSE_SIDE_KVEC)
             return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
     Program prog;
-    if ((rc = parse_program(Xd ? Tmpl::ROW_DENSE : Tmpl::ROW_CSR, expr, 1, sides, nsides, prog, g_err)))
+    if ((rc = parse_cached(Xd ? Tmpl::ROW_DENSE : Tmpl::ROW_CSR, expr, 1, sides, nsides, prog, g_err)))
         return rc;
     const int64_t m = Xd ? Xd->rows : Xs->rows, n = Xd ? Xd->cols : Xs->cols;
     if ((rc = check_sides(sides, nsides, m, n, launch, prog.side_used)))
@@ -674,7 +739,7 @@ int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, co
             return fail(FUSE_EINVAL, "out is NULL");
     }
     if (Xd)
-        return row_dense_impl(prog, program_key(prog), Xd, sides, nsides, agg, out, stream, launch,
+        return row_dense_impl(prog, prog.key, Xd, sides, nsides, agg, out, stream, launch,
                               "fuse_row_dense");
     return row_csr_impl(prog, Xs, sides, nsides, agg, out, stream, launch);
 }
@@ -721,7 +786,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         if (sides[q].kind < 0 || sides[q].kind > 3)
             return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
     Program prog;
-    if ((rc = parse_program(Tmpl::OUTER, expr, 1, sides, nsides, prog, g_err)))
+    if ((rc = parse_cached(Tmpl::OUTER, expr, 1, sides, nsides, prog, g_err)))
         return rc;
     if ((rc = check_sides(sides, nsides, X->rows, X->cols, launch, prog.side_used)))
         return rc;
@@ -793,7 +858,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     }
 
     const bool out_vec = vec2 && (!launch || aligned16(out));
-    const std::string key = std::string("outer|") + (panels ? "panels|" : "") + program_key(prog) + "|" + side_key(sides, nsides) + "|agg" +
+    const std::string key = std::string("outer|") + (panels ? "panels|" : "") + prog.key + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(mode) + (mode == 2 && out_vec ? "o" : "") + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
                             std::to_string(EPL) + "u" + std::to_string(UNR) + "b" + std::to_string(BLOCK) + "w" +
                             std::to_string(X->rowptr_is64 != 0);
@@ -956,7 +1021,12 @@ int fuse_cache_stats(int64_t *hits, int64_t *misses, double *compile_ms)
     return FUSE_OK;
 }
 
-void fuse_cache_clear(void) { fuse::Runtime::get().clear(); }
+void fuse_cache_clear(void)
+{
+    fuse::Runtime::get().clear();
+    std::lock_guard<std::mutex> lk(g_parse_mu);
+    g_parsed.clear();
+}
 
 size_t fuse_last_source(char *buf, size_t buflen)
 {
