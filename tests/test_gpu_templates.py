@@ -2,6 +2,8 @@
 variants, odd shapes and edge cases, against the oracle's operator-at-a-time
 evaluation.  Integer / index work (positions of outputs on a CSR pattern,
 per-row counts, total nnz) must be bit-exact."""
+import os
+
 import numpy as np
 import pytest
 
@@ -11,6 +13,10 @@ from exprgen import random_scalar_expr, random_row_expr
 from gpu_util import to_dev, dev_sides, dev_csr, host, assert_close
 
 pytestmark = pytest.mark.gpu
+
+# FUSE_TEST_MORE=k multiplies the number of random-expression cases (seeds) per test; the
+# default suite runs k = 1.
+MORE = max(1, int(os.environ.get("FUSE_TEST_MORE", "1")))
 
 KINDS = ["matrix", "colvec", "rowvec", "scalar"]
 
@@ -38,7 +44,7 @@ def _abs_scale(vals_none, agg, m, n):
 CELL_SHAPES = [(1, 1), (3, 5), (37, 129), (64, 256), (257, 100), (5, 4099), (1000, 3)]
 
 
-@pytest.mark.parametrize("case", range(14))
+@pytest.mark.parametrize("case", range(14 * MORE))
 def test_cell_random_expressions_all_variants(case):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(5000 + case)
@@ -124,11 +130,11 @@ def test_cell_closed_forms_on_gpu():
 
 # ------------------------------------------------------------------------- MAgg ---
 
-@pytest.mark.parametrize("case", range(6))
+@pytest.mark.parametrize("case", range(6 * MORE))
 def test_magg_random_and_equals_separate_cells(case):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(6000 + case)
-    m, n = [(1, 1), (19, 23), (300, 129), (64, 1024), (1001, 77), (2, 100001)][case]
+    m, n = [(1, 1), (19, 23), (300, 129), (64, 1024), (1001, 77), (2, 100001)][case % 6]
     k = int(rng.integers(1, 6))
     x = rng.uniform(-1.5, 1.5, size=(m, n))
     sides = [("matrix", rng.uniform(-1.5, 1.5, size=(m, n))), ("matrix", rng.uniform(-1.5, 1.5, size=(m, n))),
@@ -146,15 +152,15 @@ def test_magg_random_and_equals_separate_cells(case):
         assert_close(got[j], one[0], scale=scale, tol=1e-13, what="magg vs cell [%d]" % j)
 
 
-@pytest.mark.parametrize("case", range(6))
+@pytest.mark.parametrize("case", range(6 * MORE))
 def test_magg_with_vector_sides_and_strided_inputs(case):
     """MAgg bodies that need the 2-D form of the skeleton: row / column vector sides, views with a
     leading dimension > cols.  Same bar as the flat form, and equal to the aggregates one by one."""
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(6100 + case)
-    m, n = [(1, 1), (19, 23), (300, 129), (64, 1024), (1001, 77), (7, 5000)][case]
+    m, n = [(1, 1), (19, 23), (300, 129), (64, 1024), (1001, 77), (7, 5000)][case % 6]
     k = int(rng.integers(1, 6))
-    pad = [0, 3, 2, 0, 5, 1][case]
+    pad = [0, 3, 2, 0, 5, 1][case % 6]
     xb, yb = rng.uniform(-1.5, 1.5, size=(m, n + pad)), rng.uniform(-1.5, 1.5, size=(m, n + pad))
     x, y = xb[:, :n], yb[:, :n]
     sides = [("matrix", y), ("colvec", rng.uniform(-1.5, 1.5, size=m)), ("rowvec", rng.uniform(-1.5, 1.5, size=n)),
@@ -166,7 +172,7 @@ def test_magg_with_vector_sides_and_strided_inputs(case):
     sd = [("matrix", to_dev(yb)[:, :n]), ("colvec", to_dev(sides[1][1])), ("rowvec", to_dev(sides[2][1])),
           ("scalar", 0.7)]
     got = host(F.fuse_magg(exprs, xd, sd))
-    assert F.last_kernel().startswith("fuse_magg2d_")
+    assert F.last_kernel().startswith(("fuse_magg2d_", "fuse_cell2d_"))     # 2-D form (a cached 1-body plan keeps its name)
     ref = unfused.magg(exprs, x, sides)
     for j in range(k):
         scale = _abs_scale(unfused.cell(exprs[j], x, sides, "none"), "full", m, n)
@@ -200,7 +206,7 @@ def test_cell_bodies_without_a_matrix_operand():
 ROW_SHAPES = [(1, 1), (5, 3), (70, 10), (33, 100), (129, 101), (40, 784), (17, 1000), (9, 2048), (300, 64)]
 
 
-@pytest.mark.parametrize("case", range(18))
+@pytest.mark.parametrize("case", range(18 * MORE))
 def test_row_dense_random_expressions(case):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(7000 + case)
@@ -316,7 +322,7 @@ def test_row_csr_index_handling_is_bit_exact(csr_mapping):
         assert np.array_equal(got, cv[rows] * rv[ci])
 
 
-@pytest.mark.parametrize("case", range(12))
+@pytest.mark.parametrize("case", range(12 * MORE))
 def test_row_csr_random_sparse_safe_expressions(case, csr_mapping):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(8000 + case)
@@ -367,7 +373,7 @@ def outer_mapping(request, monkeypatch):
     return request.param
 
 
-@pytest.mark.parametrize("case", range(12))
+@pytest.mark.parametrize("case", range(12 * MORE))
 def test_outer_random_expressions(case, outer_mapping):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(9000 + case)
@@ -459,7 +465,7 @@ def test_outer_mm_on_all_patterns(agg):
             assert not got.reshape(-1, r)[empty].any()
 
 
-@pytest.mark.parametrize("case", range(8))
+@pytest.mark.parametrize("case", range(8 * MORE))
 def test_outer_mm_random_expressions(case):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(9500 + case)
@@ -534,7 +540,7 @@ def test_row_long_chain_expression(nops):
 
 # ------------------------------------------------- Cell / MAgg over a sparse X ---
 
-@pytest.mark.parametrize("case", range(10))
+@pytest.mark.parametrize("case", range(10 * MORE))
 def test_sparse_cell_and_magg_random_expressions(case, csr_mapping):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(9700 + case)
