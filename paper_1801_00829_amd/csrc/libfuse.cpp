@@ -569,11 +569,13 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     // for lane groups, 10 per row 264 against 234, 100 per row 344 against 267.
     // FUSE_CSR_STREAM: 0 never, 1 always, 2 by this rule.
     const int stream_mode = env_int("FUSE_CSR_STREAM", 2);
-    const bool streaming = stream_mode == 1 || (stream_mode == 2 && G * C <= 8);
     const int SC = 4;                                    // cells per lane of the streaming skeleton
+    // bodies that never look at the row (no row aggregate, no per-row side, one value per cell)
+    // run the streaming skeleton's flat form over the cell arrays, whatever the row lengths
     bool need_rid = prog.nred > 0 || ac == 2 || !prog.result_vec;
     for (int k = 0; k < nsides; ++k)
         need_rid |= prog.side_used[k] && (sides[k].kind == FUSE_SIDE_MATRIX || sides[k].kind == FUSE_SIDE_COLVEC);
+    const bool streaming = stream_mode == 1 || (stream_mode == 2 && (G * C <= 8 || !need_rid));
 
     // LDS plan: the column accumulator first, then staged row-vector sides if they fit
     int nrv = 0;
@@ -630,8 +632,12 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
 
     const int cus = rt.num_cus();
     const int NW = BLOCK / 64;
+    if (streaming && !need_rid && X->nnz == 0)
+        return zero_fill(fn, out, ac == 0 ? 0 : out_count, stream);
     const int64_t rows_per_iter = streaming ? NW : (int64_t)(64 / G) * RS * NW;
     int64_t gx = (m + rows_per_iter - 1) / rows_per_iter;
+    if (streaming && !need_rid)
+        gx = (X->nnz + (int64_t)64 * SC * NW - 1) / ((int64_t)64 * SC * NW);
     gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CSR_BLOCKS_PER_CU", 1)));
     Workspace ws;
     const size_t need = ac == 3 ? (size_t)gx * (size_t)n : (size_t)gx * prog.roots.size();
