@@ -172,7 +172,7 @@ int fuse_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
  * zero wherever X has no stored cell (products with X, zero-preserving unaries,
  * sums of such), otherwise FUSE_EDESC.
  *   fuse_cell_csr: agg NONE -> nnz values on X's pattern; ROW -> rows(X) sums;
- *                  COL / COL_T -> cols(X) sums (cols <= 6144); FULL -> 1 value.
+ *                  COL / COL_T -> cols(X) sums; FULL -> 1 value.
  *   fuse_magg_csr: k full aggregates in one scan of X; out_k[j] = sum of body j.
  */
 int fuse_cell_csr(const fuse_expr *expr, const fuse_csr *X, const fuse_side *sides, int nsides,
@@ -203,10 +203,10 @@ int fuse_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
  * aggregated or returned must be zero wherever X has no stored cell (products
  * with X, zero-preserving unaries, sums of such); otherwise FUSE_EDESC.
  * With CSR input and COL / COL_T the order in which a block's rows are added
- * to a column sum is not fixed (shared-memory atomics); all else is deterministic.
+ * to a column sum is not fixed (shared-memory atomics up to 7488 columns, fp64
+ * atomics on the zeroed output beyond); all else is deterministic.
  * Limits of this build: vector results / ROWSUM / DOT need cols <= 2048 for
- * dense input (FUSE_EUNSUPPORTED beyond); CSR with COL / COL_T needs
- * cols <= 6144.
+ * dense input (FUSE_EUNSUPPORTED beyond).
  */
 int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
              const fuse_side *sides, int nsides, int agg, double *out, void *stream);

@@ -582,17 +582,17 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     for (int k = 0; k < nsides; ++k)
         nrv += prog.side_used[k] && sides[k].kind == FUSE_SIDE_ROWVEC;
     const int64_t lds_budget = 64000;
-    if (ac == 3 && n * 8 > lds_budget - 4096)
-        return fail(FUSE_EUNSUPPORTED, "CSR Row with column aggregation needs cols <= " +
-                                           std::to_string((lds_budget - 4096) / 8));
-    const bool stage_rv = nrv > 0 && ((ac == 3 ? n : 0) + (int64_t)nrv * n) * 8 <= lds_budget - 1024;
-    const int64_t npad = (ac == 3 || stage_rv) ? std::max<int64_t>(n, 1) : 1;
+    // column sums: a per-block LDS vector while it fits (cols <= 7488), else fp64 atomics on the output
+    const bool cols_global = ac == 3 && n * 8 > lds_budget - 4096;
+    const bool cols_lds = ac == 3 && !cols_global;
+    const bool stage_rv = nrv > 0 && ((cols_lds ? n : 0) + (int64_t)nrv * n) * 8 <= lds_budget - 1024;
+    const int64_t npad = (cols_lds || stage_rv) ? std::max<int64_t>(n, 1) : 1;
 
     const int nt = env_int("FUSE_CSR_NT", streaming ? 1 : 0);
     const std::string key = std::string("rowcsr|") + prog.key + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(ac) + (streaming ? "|stream" + std::to_string(SC) + "r" + std::to_string(need_rid)
                                                             : "|g" + std::to_string(G) + "c" + std::to_string(C) + "r" + std::to_string(RS)) + "b" +
-                            std::to_string(BLOCK) + "p" + std::to_string(npad) + "s" + std::to_string(stage_rv) +
+                            std::to_string(BLOCK) + "p" + std::to_string(npad) + "s" + std::to_string(stage_rv) + (cols_global ? "G" : "") +
                             "w" + std::to_string(X->rowptr_is64 != 0) + std::to_string(m < (1LL << 30)) + "nt" +
                             std::to_string(nt);
     std::shared_ptr<Plan> plan;
@@ -605,6 +605,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
         s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_C " + std::to_string(streaming ? SC : C) +
              "\n#define FUSE_RS " + std::to_string(RS) + "\n#define FUSE_NEED_RID " + std::to_string(need_rid) +
+             "\n#define FUSE_COLS_GLOBAL " + std::to_string(cols_global) +
              "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_AGG " + std::to_string(ac) +
              "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) + "\n#define FUSE_ROW32 " +
              std::to_string(m < (1LL << 30)) + "\n#define FUSE_NPAD " +
@@ -640,7 +641,9 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
         gx = (X->nnz + (int64_t)64 * SC * NW - 1) / ((int64_t)64 * SC * NW);
     gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CSR_BLOCKS_PER_CU", 1)));
     Workspace ws;
-    const size_t need = ac == 3 ? (size_t)gx * (size_t)n : (size_t)gx * prog.roots.size();
+    const size_t need = cols_lds ? (size_t)gx * (size_t)n : (size_t)gx * prog.roots.size();
+    if (cols_global && (rc = zero_fill(fn, out, n, stream)))
+        return rc;
     if ((rc = rt.workspace(stream, need, ws, g_err)))
         return rc;
     fuse_kargs A;
@@ -664,7 +667,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     fill_side_args(A, sides, nsides);
     if ((rc = rt.launch(fn.main, (unsigned)gx, 1, BLOCK, stream, &A, sizeof A, g_err)))
         return rc;
-    if (ac == 3)
+    if (cols_lds)
         return run_combine(fn, ws.partials, (int)gx, (int)n, out, stream);
     return 0;
 }

@@ -350,6 +350,26 @@ def test_row_csr_random_sparse_safe_expressions(case, csr_mapping):
                      what="row csr %s" % agg)
 
 
+def test_row_csr_column_sums_of_wide_matrices(csr_mapping):
+    """More columns than a per-block shared-memory vector holds: column sums go through fp64
+    atomics on the output.  Counts are exact, t(X)(Xv) within the usual bar."""
+    import paper_1801_00829_amd as F
+    from oracle import plans
+    for (m, n, d) in ((3000, 20000, 0.0005), (500, 100001, 0.0002), (40, 9000, 0.3)):
+        rp, ci, va = W.csr_bernoulli(m, n, d, 4242)
+        print("wide csr", (m, n), "nnz", int(rp[-1]), csr_mapping, flush=True)
+        xd = dev_csr(rp, ci, np.ones_like(va), (m, n))
+        assert np.array_equal(host(F.fuse_row([("main",)], xd, [], "col")), np.bincount(ci, minlength=n).astype(np.float64))
+        assert "#define FUSE_COLS_GLOBAL 1" in F.last_source()
+        v = np.random.default_rng(5).normal(size=n)
+        expr = [("main",), ("side", 0), ("dot",), ("main",), ("mul",)]
+        got = host(F.fuse_row(expr, dev_csr(rp, ci, va, (m, n)), [("rowvec", to_dev(v))], "col_t"))
+        x = ops.make_csr(rp, ci, va, (m, n))
+        ref = plans.row_csr_tx_xv(x, v)
+        scale = max(np.abs(ops.csr_t_matvec(x, ops.csr_matvec(x, np.abs(v)))).max(), 1e-300)
+        assert_close(got, ref, scale=scale, what="wide csr t(X)(Xv)")
+
+
 def test_row_csr_rejects_programs_that_are_not_sparse_safe():
     import paper_1801_00829_amd as F
     rp, ci, va = W.csr_bernoulli(10, 10, 0.3, 1)
