@@ -205,8 +205,8 @@ int fuse_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
  * With CSR input and COL / COL_T the order in which a block's rows are added
  * to a column sum is not fixed (shared-memory atomics up to 7488 columns, fp64
  * atomics on the zeroed output beyond); all else is deterministic.
- * Limits of this build: vector results / ROWSUM / DOT need cols <= 2048 for
- * dense input (FUSE_EUNSUPPORTED beyond).
+ * Limits of this build: bodies with ROWSUM / DOT need cols <= 32768 for dense
+ * input, bodies with k-vectors cols <= 2048 (FUSE_EUNSUPPORTED beyond).
  */
 int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
              const fuse_side *sides, int nsides, int agg, double *out, void *stream);

@@ -324,12 +324,22 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         G <<= 1;
     int64_t epl64 = (nvec + G - 1) / G;
     int stripes = 1;
+    int WPR = 1;                 // waves per row (> 1: the whole block owns one row)
     if (epl64 > 16) {
-        if (prog.nstage > 0)
-            return fail(FUSE_EUNSUPPORTED, "Row bodies with ROWSUM / DOT need cols <= " +
-                                               std::to_string(64 * 16 * VEC) + " for dense input");
-        epl64 = 16;
-        stripes = (int)((n + (int64_t)64 * 16 * VEC - 1) / ((int64_t)64 * 16 * VEC));
+        if (prog.nstage > 0) {
+            // per-row reductions over a row wider than one wave's registers: 2 .. 16 waves per row
+            while (WPR < 16 && (nvec + (int64_t)64 * WPR - 1) / ((int64_t)64 * WPR) > 16)
+                WPR <<= 1;
+            epl64 = (nvec + (int64_t)64 * WPR - 1) / ((int64_t)64 * WPR);
+            if (epl64 > 16 || kd > 0)
+                return fail(FUSE_EUNSUPPORTED, kd > 0 ? "Row bodies with k-vectors need cols <= " + std::to_string(64 * 16 * VEC) +
+                                                            " for dense input"
+                                                      : "Row bodies with ROWSUM / DOT need cols <= " +
+                                                            std::to_string(64 * 16 * 16 * VEC) + " for dense input");
+        } else {
+            epl64 = 16;
+            stripes = (int)((n + (int64_t)64 * 16 * VEC - 1) / ((int64_t)64 * 16 * VEC));
+        }
     }
     if (epl64 < 1)
         epl64 = 1;
@@ -340,11 +350,15 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     int RS = env_int("FUSE_ROW_RS", 0);
     if (RS <= 0)
         RS = EPL >= 8 ? 1 : (EPL >= 3 ? 2 : 4);
-    const int BLOCK = 256;
+    const int BLOCK = WPR > 1 ? std::max(128, 64 * WPR) : 256;
+    if (WPR > 1 && BLOCK != 64 * WPR)
+        WPR = BLOCK / 64;          // at least two waves per block
+    if (WPR > 1)
+        RS = 1;
 
     const std::string key = std::string("rowdense|") + pkey + "|rk" + std::to_string(rk) + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(ac) + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
-                            std::to_string(EPL) + "r" + std::to_string(RS) + "nt" +
+                            std::to_string(EPL) + "r" + std::to_string(RS) + "w" + std::to_string(WPR) + "nt" +
                             std::to_string(env_int("FUSE_NT", 1));
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, name_prefix, [&](const std::string &name) {
@@ -354,7 +368,8 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
         s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_EPL " + std::to_string(EPL) +
              "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_RS " + std::to_string(RS) +
-             "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_AGG " + std::to_string(ac) + "\n";
+             "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_AGG " + std::to_string(ac) +
+             "\n#define FUSE_WPR " + std::to_string(WPR) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_row_body(prog);
         s += kSrcRowDense;
@@ -382,10 +397,11 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         return zero_fill(fn, out, out_count, stream);
 
     const int NW = BLOCK / 64;
-    const int64_t rows_per_iter = (int64_t)(64 / G) * RS * NW;
+    const int64_t rows_per_iter = WPR > 1 ? RS : (int64_t)(64 / G) * RS * NW;
     const int cus = rt.num_cus();
     int64_t gx = (m + rows_per_iter - 1) / rows_per_iter;
-    const int64_t cap = std::max<int64_t>(1, (int64_t)cus * env_int("FUSE_ROW_BLOCKS_PER_CU", 2) / stripes);
+    const int bpc = WPR > 1 ? std::max(1, 16 / WPR) : env_int("FUSE_ROW_BLOCKS_PER_CU", 2);
+    const int64_t cap = std::max<int64_t>(1, (int64_t)cus * bpc / stripes);
     gx = std::min(gx, cap);
     Workspace ws;
     const int64_t nacc = rk == KIND_VK ? kd : 1;      // running sums per column

@@ -226,6 +226,31 @@ def test_row_dense_random_expressions(case):
         assert_close(got, ref, scale=scale, tol=1e-9, what="row dense %s" % agg)
 
 
+@pytest.mark.parametrize("shape", [(7, 2050), (33, 3000), (12, 4097), (5, 9000), (3, 20000), (2, 32768)])
+def test_row_dense_wide_rows_with_reductions(shape):
+    """Rows wider than one wave's registers (2048 columns): several waves own a row and
+    exchange their partial row aggregates through shared memory."""
+    import paper_1801_00829_amd as F
+    m, n = shape
+    rng = np.random.default_rng(7100 + n)
+    x = rng.normal(size=(m, n))
+    sides = _sides(rng, m, n)
+    xd, sd = to_dev(x), dev_sides(sides)
+    exprs = {"V": [("main",), ("side", 2), ("dot",), ("main",), ("mul",), ("main",), ("rowsum",), ("side", 1), ("mul",), ("add",)],
+             "S": [("main",), ("side", 0), ("mul",), ("rowsum",), ("main",), ("main",), ("rowsum",), ("sub",), ("pow2",), ("rowsum",), ("add",)]}
+    for want, expr in exprs.items():
+        none_ref = unfused.row_dense(expr, x, sides, "none")
+        for agg in (("none", "row", "col_t", "full") if want == "V" else ("none", "full")):
+            print("row wide", shape, want, agg, flush=True)
+            got = host(F.fuse_row(expr, xd, sd, agg))
+            ref = unfused.row_dense(expr, x, sides, agg)
+            scale = _abs_scale(none_ref, agg.replace("col_t", "col"), m, n) if want == "V" else \
+                (None if agg == "none" else max(np.abs(none_ref).sum(), 1e-300))
+            assert_close(got.reshape(ref.shape), ref, scale=scale, tol=1e-9, what="row wide %s %s" % (want, agg))
+    src = F.last_source()
+    assert int(src[src.index("#define FUSE_WPR ") + 17:].split()[0]) > 1          # the generator's own definition
+
+
 def test_row_dense_closed_forms_and_odd_layouts():
     import torch
     import paper_1801_00829_amd as F
@@ -253,9 +278,12 @@ def test_row_dense_empty_and_limits():
     x = torch.empty((0, 8), dtype=torch.float64, device="cuda")
     v = torch.ones(8, dtype=torch.float64, device="cuda")
     assert host(F.fuse_row(expr, x, [("rowvec", v)], "col_t")).tolist() == [0.0] * 8
-    big = torch.ones((2, 4098), dtype=torch.float64, device="cuda")
+    big = torch.ones((2, 4098), dtype=torch.float64, device="cuda")          # several waves per row
+    got = host(F.fuse_row(expr, big, [("rowvec", torch.ones(4098, dtype=torch.float64, device="cuda"))], "col_t"))
+    assert got.tolist() == [2.0 * 4098] * 4098
+    huge = torch.ones((2, 40000), dtype=torch.float64, device="cuda")
     with pytest.raises(F.FuseError) as e:
-        F.fuse_row(expr, big, [("rowvec", torch.ones(4098, dtype=torch.float64, device="cuda"))], "col_t")
+        F.fuse_row(expr, huge, [("rowvec", torch.ones(40000, dtype=torch.float64, device="cuda"))], "col_t")
     assert e.value.code == -7
 
 

@@ -174,8 +174,10 @@ def test_row_type_checking_and_sparse_safety(F):
         assert e.value.code == -3 and "sparse-safe" in str(e.value)
     # dense Row limit on the width of reductions
     with pytest.raises(F.FuseError) as e:
-        F.prepare_row(dot_v, (10, 5000), [("rowvec", None)], "none")
+        F.prepare_row(dot_v, (10, 40000), [("rowvec", None)], "none")
     assert e.value.code == -7
+    F.prepare_row(dot_v, (10, 5000), [("rowvec", None)], "none")           # several waves per row
+    assert "#define FUSE_WPR 4" in F.last_source()
 
 
 def test_row_matrix_rhs_type_checking(F):
