@@ -261,6 +261,7 @@ std::string program_key(const Program &prog)
     k += "|";
     for (int r : prog.roots)
         k += std::to_string(r) + ",";
+    k += "|k" + std::to_string(prog.kdim) + "r" + std::to_string(prog.result_kind);    // widths the tokens do not show
     return k;
 }
 

@@ -325,17 +325,24 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     int64_t epl64 = (nvec + G - 1) / G;
     int stripes = 1;
     int WPR = 1;                 // waves per row (> 1: the whole block owns one row)
-    if (epl64 > 16) {
-        if (prog.nstage > 0) {
+    // registers a lane spends per owned column: the row itself, and with k-vectors the k entries of the
+    // right-hand side and of the accumulators
+    auto fits = [&](int64_t epl) { return epl <= 16 && (kd == 0 || epl * VEC * kd <= 48); };
+    if (!fits(epl64)) {
+        if (prog.nstage > 0 || kd > 0) {
             // per-row reductions over a row wider than one wave's registers: 2 .. 16 waves per row
-            while (WPR < 16 && (nvec + (int64_t)64 * WPR - 1) / ((int64_t)64 * WPR) > 16)
+            G = 64;
+            epl64 = (nvec + 63) / 64;
+            while (WPR < 16 && !fits(epl64)) {
                 WPR <<= 1;
-            epl64 = (nvec + (int64_t)64 * WPR - 1) / ((int64_t)64 * WPR);
-            if (epl64 > 16 || kd > 0)
-                return fail(FUSE_EUNSUPPORTED, kd > 0 ? "Row bodies with k-vectors need cols <= " + std::to_string(64 * 16 * VEC) +
-                                                            " for dense input"
-                                                      : "Row bodies with ROWSUM / DOT need cols <= " +
-                                                            std::to_string(64 * 16 * 16 * VEC) + " for dense input");
+                epl64 = (nvec + (int64_t)64 * WPR - 1) / ((int64_t)64 * WPR);
+            }
+            if (!fits(epl64))
+                return fail(FUSE_EUNSUPPORTED,
+                            kd > 0 ? "Row bodies with k-vectors need ceil(cols / " + std::to_string(1024 * VEC) + ") * " +
+                                         std::to_string(VEC) + " * k <= 48 in this build"
+                                   : "Row bodies with ROWSUM / DOT need cols <= " + std::to_string(64 * 16 * 16 * VEC) +
+                                         " for dense input");
         } else {
             epl64 = 16;
             stripes = (int)((n + (int64_t)64 * 16 * VEC - 1) / ((int64_t)64 * 16 * VEC));
@@ -344,9 +351,6 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     if (epl64 < 1)
         epl64 = 1;
     const int EPL = (int)epl64;
-    if (kd > 0 && (stripes > 1 || EPL * VEC * kd > 48))
-        return fail(FUSE_EUNSUPPORTED, "Row bodies with k-vectors need ceil(cols / " + std::to_string(64 * VEC) +
-                                           ") * " + std::to_string(VEC) + " * k <= 48 in this build");
     int RS = env_int("FUSE_ROW_RS", 0);
     if (RS <= 0)
         RS = EPL >= 8 ? 1 : (EPL >= 3 ? 2 : 4);

@@ -646,7 +646,7 @@ TXXV = [("main",), ("main",), ("side", 0), ("matmult",), ("outerk",)]           
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (70, 10, 3), (333, 100, 4), (129, 101, 2), (64, 1000, 2), (50, 784, 1),
-                                   (500, 37, 16)])
+                                   (500, 37, 16), (120, 784, 10), (33, 2048, 16), (40, 1000, 8), (17, 4096, 5), (9, 3000, 3)])
 def test_row_matrix_rhs_chain_and_mlogreg_core(shape):
     """t(X) %*% (X %*% V) with an n x k right-hand side (Fig. 8g) and the multinomial logistic
     regression core H = t(X) (Q - P * rowSums(Q)), Q = P * (X V)  (Sec. 2.2, second example)."""
@@ -691,9 +691,9 @@ def test_row_matrix_rhs_strided_sides_and_limits():
                           "col_t")).reshape(n, k)
     assert_close(got, plans.mlogreg_core(x, v, p), scale=np.abs(x).T @ (np.abs(x) @ np.abs(v)) * 2 * k, what="strided rhs")
     import torch
-    with pytest.raises(F.FuseError) as e:       # too many columns for the register-resident form
-        F.fuse_row(TXXV, torch.ones((4, 2000), dtype=torch.float64, device="cuda"),
-                   [("rhs", torch.ones((2000, 8), dtype=torch.float64, device="cuda"))], "col_t")
+    with pytest.raises(F.FuseError) as e:       # too many columns x k for the register-resident form
+        F.fuse_row(TXXV, torch.ones((4, 6000), dtype=torch.float64, device="cuda"),
+                   [("rhs", torch.ones((6000, 16), dtype=torch.float64, device="cuda"))], "col_t")
     assert e.value.code == -7
     with pytest.raises(F.FuseError) as e:       # shapes: the right-hand side must have cols(X) rows
         F.fuse_row(TXXV, to_dev(x), [("rhs", to_dev(np.ones((n + 1, k))))], "col_t")

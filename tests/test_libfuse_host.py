@@ -207,8 +207,14 @@ def test_row_matrix_rhs_type_checking(F):
         with pytest.raises(F.FuseError) as e:
             F.prepare_row(expr, (1000, 100), sides, agg)
         assert e.value.code == code, (expr, sides, agg, e.value.code, str(e.value))
-    with pytest.raises(F.FuseError) as e:                                 # register budget: ceil(n/128)*2*k <= 48
-        F.prepare_row(txxv, (100, 2000), [("rhs", (2000, 4))], "col_t")
+    F.prepare_row(txxv, (100, 2000), [("rhs", (2000, 4))], "col_t")         # several waves per row
+    assert "#define FUSE_WPR 4" in F.last_source()
+    F.prepare_row(txxv, (100, 784), [("rhs", (784, 10))], "col_t")           # the MLogreg shape of Mnist
+    assert "#define FUSE_KDIM 10" in F.last_source()
+    F.prepare_row(txxv, (100, 1000), [("rhs", (1000, 8))], "col_t")          # same launch shape, other k: its own plan
+    assert "#define FUSE_KDIM 8" in F.last_source()
+    with pytest.raises(F.FuseError) as e:                                 # register budget: ceil(n/2048)*2*k <= 48
+        F.prepare_row(txxv, (100, 6000), [("rhs", (6000, 16))], "col_t")
     assert e.value.code == -7
     with pytest.raises(F.FuseError) as e:                                 # CSR main input
         F.prepare_row(xv, (1000, 100), [("rhs", (100, 4))], "none", nnz=500)
