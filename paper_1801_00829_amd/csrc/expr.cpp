@@ -417,6 +417,14 @@ std::string emit_row_body(const Program &prog)
                    (prog.result_kind == KIND_V ? em.gen(prog.roots[j]) : std::string("0.0")) + ";\n";
     }
     src += "}\n";
+    // the k-vector factor of a row (x) k-vector result on its own (the matrix-unit skeleton forms the
+    // outer products itself)
+    src += "__device__ __forceinline__ void fuse_outer_kvec(const double *rsc, const double *kv, const double *red,\n"
+           "                                                double *r)\n{\n";
+    for (int j = 0; j < kd; ++j)
+        src += "    r[" + std::to_string(j) + "] = " +
+               (prog.result_kind == KIND_VK ? em.gen(prog.nodes[root].b, j) : std::string("0.0")) + ";\n";
+    src += "}\n";
     src += "__device__ __forceinline__ double fuse_final_elem(double a, const double *sv, const double *rsc,\n"
            "                                                  const double *kv, const double *red)\n{\n    return " +
            (prog.result_kind == KIND_V ? em.gen(root) : std::string("0.0")) + ";\n}\n";

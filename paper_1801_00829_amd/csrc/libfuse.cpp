@@ -31,6 +31,9 @@ const char *kSrcCell =
 const char *kSrcRowDense =
 #include "skel_row_dense.inc"
     ;
+const char *kSrcRowMfma =
+#include "skel_row_mfma.inc"
+    ;
 const char *kSrcRowCsr =
 #include "skel_row_csr.inc"
     ;
@@ -283,6 +286,100 @@ int agg_code(int agg)
     return -1;
 }
 
+// ------------------------------------------------------------ row (dense, MFMA) --
+// Bodies  t(X) %*% W  with  W_i = f(X_i %*% V, per-row sides):  exactly one MATMULT of the main
+// input with a right-hand side, and an OUTERK of the main input with a k-vector as the result.
+bool mfma_pattern(const Program &prog, const fuse_side *sides, int nsides, int &vside)
+{
+    if (prog.result_kind != KIND_VK || prog.nstage != 1 || prog.reductions.size() != 1 || prog.roots.size() != 1)
+        return false;
+    const Node &mm = prog.nodes[prog.reductions[0]];
+    const Node &root = prog.nodes[prog.roots[0]];
+    if (mm.op != FUSE_OP_MATMULT || root.op != FUSE_OP_OUTERK)
+        return false;
+    if (prog.nodes[mm.a].op != FUSE_OP_MAIN || prog.nodes[root.a].op != FUSE_OP_MAIN)
+        return false;
+    const Node &v = prog.nodes[mm.b];
+    if (v.op != FUSE_OP_SIDE || v.arg < 0 || v.arg >= nsides || sides[v.arg].kind != FUSE_SIDE_RHS)
+        return false;
+    for (int q = 0; q < nsides; ++q)
+        if (prog.side_used[q] && (sides[q].kind == FUSE_SIDE_MATRIX || sides[q].kind == FUSE_SIDE_ROWVEC))
+            return false;
+    vside = v.arg;
+    return true;
+}
+
+int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense *X, const fuse_side *sides,
+                  int nsides, int vside, double *out, hipStream_t stream, bool launch)
+{
+    Runtime &rt = Runtime::get();
+    const int64_t m = X->rows, n = X->cols;
+    const int kd = prog.kdim;
+    const bool vec2 = (n % 2 == 0) && (X->ld % 2 == 0) && (!launch || aligned16(X->data));
+    const int VEC = vec2 ? 2 : 1;
+    const int64_t nct = (n + 15) / 16;                       // 16-column tiles
+    const int64_t np = nct * 16 + 1;                         // odd LDS row pitch
+    const int64_t nvec = (n + VEC - 1) / VEC;
+    // waves per block (FUSE_MFMA_WAVES, default 8), fewer if the LDS next to the tile does not hold that many
+    // partial products (16 x 17 doubles each)
+    int NWAVE = env_int("FUSE_MFMA_WAVES", 8);
+    if (NWAVE != 4 && NWAVE != 8 && NWAVE != 16)
+        NWAVE = 8;
+    const int ns_ = std::max(nsides, 1);
+    auto lds_bytes = [&](int nw) { return (16 * np + (int64_t)(nw + 2 + ns_) * 272 + (int64_t)ns_ * 16) * 8; };
+    while (NWAVE > 4 && lds_bytes(NWAVE) > 158 * 1024)
+        NWAVE >>= 1;
+    if (lds_bytes(NWAVE) > 158 * 1024)
+        return fail(FUSE_EUNSUPPORTED, "internal: matrix-unit Row form chosen for a row tile that does not fit in LDS");
+    const int BLOCK = 64 * NWAVE;
+    const int64_t nld = (nvec + BLOCK / 16 - 1) / (BLOCK / 16);
+    const std::string key = std::string("rowmfma|") + pkey + "|" + side_key(sides, nsides) + "|v" + std::to_string(VEC) +
+                            "n" + std::to_string(nct) + "w" + std::to_string(NWAVE) + "nt" + std::to_string(env_int("FUSE_NT", 1));
+    std::shared_ptr<Plan> plan;
+    int rc = rt.plan(key, "fuse_row_mfma", [&](const std::string &name) {
+        std::string s = kSrcArgs;
+        s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 1)) + "\n";
+        s += kSrcCommon;
+        s += "#define FUSE_KERNEL_NAME " + name + "\n";
+        s += "#define FUSE_NWAVE " + std::to_string(NWAVE) + "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_NP " + std::to_string(np) +
+             "\n#define FUSE_NCT " + std::to_string(nct) + "\n#define FUSE_NLD " + std::to_string(nld) +
+             "\n#define FUSE_VSIDE " + std::to_string(vside) + "\n";
+        s += side_tables(sides, nsides, prog.side_used);
+        s += emit_row_body(prog);
+        s += kSrcRowMfma;
+        g_last_source = s;
+        return s;
+    }, plan, g_err);
+    if (rc)
+        return rc;
+    g_last_kernel = plan->kernel_name;
+    if (!launch)
+        return 0;
+    Plan::Loaded fn;
+    if ((rc = rt.load(*plan, fn, g_err)))
+        return rc;
+    if (m == 0 || n == 0)
+        return zero_fill(fn, out, n * kd, stream);
+    const int64_t ntiles = (m + 15) / 16;
+    const int64_t gx = std::max<int64_t>(1, std::min<int64_t>(ntiles, rt.num_cus()));
+    Workspace ws;
+    if ((rc = rt.workspace(stream, (size_t)gx * (size_t)(n * kd), ws, g_err)))
+        return rc;
+    fuse_kargs A;
+    std::memset(&A, 0, sizeof A);
+    A.x = X->data;
+    A.m = m;
+    A.n = n;
+    A.ld = X->ld;
+    A.out = out;
+    A.partials = ws.partials;
+    A.ticket = ws.ticket;
+    fill_side_args(A, sides, nsides);
+    if ((rc = rt.launch(fn.main, (unsigned)gx, 1, BLOCK, stream, &A, sizeof A, g_err)))
+        return rc;
+    return run_combine(fn, ws.partials, (int)gx, (int)(n * kd), out, stream);
+}
+
 // ------------------------------------------------------------------ row (dense) --
 // Shared by fuse_row (dense) and by Cell bodies that need the 2-D form.
 int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dense *X,
@@ -300,6 +397,18 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     if (rk == KIND_VK && ac != 3)
         return fail(FUSE_EDESC, "an OUTERK result needs FUSE_AGG_COL / FUSE_AGG_COL_T");
     const int kd = prog.kdim;
+
+    // matrix-unit form: from FUSE_MFMA_MIN_K classes on, while 16 rows of X fit in LDS (about 1200 columns)
+    {
+        int vside = -1;
+        // (measured against the vector form: equal at k = 4 for n = 784, 2.6x faster at k = 8 for n = 256,
+        //  3.2x at k = 10 for n = 784; slower for k = 4 at n = 100 and n = 1000)
+        const int min_k = env_int("FUSE_MFMA_MIN_K", 5);
+        const int64_t tile_bytes = (16 * ((n + 15) / 16 * 16 + 1) + (int64_t)(4 + 2 + std::max(nsides, 1)) * 272 + 128) * 8;
+        if (ac == 3 && min_k > 0 && kd >= min_k && n >= 16 && tile_bytes <= 158 * 1024 &&
+            mfma_pattern(prog, sides, nsides, vside))
+            return row_mfma_impl(prog, pkey, X, sides, nsides, vside, out, stream, launch);
+    }
 
     // vector width: 16-byte loads need even strides and aligned bases
     bool vec2 = (n % 2 == 0) && (X->ld % 2 == 0) && (!launch || aligned16(X->data));

@@ -645,9 +645,18 @@ MLOGREG = [("main",)] + MLOG_Q + [("side", 1)] + MLOG_Q + [("rowsum",), ("mul",)
 TXXV = [("main",), ("main",), ("side", 0), ("matmult",), ("outerk",)]                     # t(X) (X V)
 
 
+@pytest.fixture(params=["vector", "matrix_units"])
+def rhs_form(request, monkeypatch):
+    """Both forms of t(X) (f(X V)) bodies: k-vectors on the vector ALUs (k butterflies per row), or the
+    two products on the fp64 matrix units (by default from 5 classes on, while 16 rows fit in LDS)."""
+    monkeypatch.setenv("FUSE_MFMA_MIN_K", "1" if request.param == "matrix_units" else "0")
+    return request.param
+
+
 @pytest.mark.parametrize("shape", [(1, 1, 1), (70, 10, 3), (333, 100, 4), (129, 101, 2), (64, 1000, 2), (50, 784, 1),
-                                   (500, 37, 16), (120, 784, 10), (33, 2048, 16), (40, 1000, 8), (17, 4096, 5), (9, 3000, 3)])
-def test_row_matrix_rhs_chain_and_mlogreg_core(shape):
+                                   (500, 37, 16), (120, 784, 10), (33, 2048, 16), (40, 1000, 8), (17, 4096, 5), (9, 3000, 3),
+                                   (4100, 17, 7), (16, 16, 16), (15, 1199, 2)])
+def test_row_matrix_rhs_chain_and_mlogreg_core(shape, rhs_form):
     """t(X) %*% (X %*% V) with an n x k right-hand side (Fig. 8g) and the multinomial logistic
     regression core H = t(X) (Q - P * rowSums(Q)), Q = P * (X V)  (Sec. 2.2, second example)."""
     import paper_1801_00829_amd as F
@@ -662,6 +671,8 @@ def test_row_matrix_rhs_chain_and_mlogreg_core(shape):
     scale = max((absx.T @ (absx @ absv)).max(), 1e-300)
     got = host(F.fuse_row(TXXV, xd, sd, "col_t")).reshape(n, k)
     assert_close(got, plans.row_tx_xv_matrix(x, v), scale=scale, what="t(X)(XV)")
+    if 16 <= n <= 1000:
+        assert F.last_kernel().startswith("fuse_row_mfma_") == (rhs_form == "matrix_units")
     got = host(F.fuse_row(MLOGREG, xd, sd, "col_t")).reshape(n, k)
     assert_close(got, plans.mlogreg_core(x, v, p), scale=2 * k * scale, what="mlogreg core")
     assert_close(got, unfused.row_dense(MLOGREG, x, [("rhs", v), ("kvec", p)], "col_t"), scale=2 * k * scale,
@@ -679,12 +690,16 @@ def test_row_matrix_rhs_chain_and_mlogreg_core(shape):
                  scale=(absx @ absv).sum(1).max(), what="rowSums(Q)")
 
 
-def test_row_matrix_rhs_strided_sides_and_limits():
+def test_row_matrix_rhs_strided_sides_and_limits(rhs_form):
     import paper_1801_00829_amd as F
     from oracle import plans
     rng = np.random.default_rng(72)
     m, n, k = 200, 50, 3
-    x = rng.normal(size=(m, n))
+    xb = rng.normal(size=(m, n + 3))
+    x = xb[:, :n]
+    # a view of X with a leading dimension > cols and an odd column count elsewhere
+    got = host(F.fuse_row(TXXV, to_dev(xb)[:, :n], [("rhs", to_dev(rng.normal(size=(n, k))))], "col_t"))
+    assert got.size == n * k
     vb, pb = rng.normal(size=(n, k + 2)), rng.uniform(size=(m, k + 5))
     v, p = vb[:, 1:1 + k], pb[:, 2:2 + k]
     got = host(F.fuse_row(MLOGREG, to_dev(x), [("rhs", to_dev(vb)[:, 1:1 + k]), ("kvec", to_dev(pb)[:, 2:2 + k])],
