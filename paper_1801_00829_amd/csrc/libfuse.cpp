@@ -361,7 +361,12 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
     if (m == 0 || n == 0)
         return zero_fill(fn, out, n * kd, stream);
     const int64_t ntiles = (m + 15) / 16;
-    const int64_t gx = std::max<int64_t>(1, std::min<int64_t>(ntiles, rt.num_cus()));
+    // as many blocks per CU as their tiles fit in LDS (and the register file: 512 / waves-per-SIMD): the phases
+    // of one block (tile store, Q, body, H) then overlap with another block's
+    const int64_t by_lds = std::max<int64_t>(1, (158 * 1024) / lds_bytes(NWAVE));
+    const int64_t bpc = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(by_lds, 16 / NWAVE),
+                                                            env_int("FUSE_MFMA_BLOCKS_PER_CU", 4)));
+    const int64_t gx = std::max<int64_t>(1, std::min<int64_t>(ntiles, (int64_t)rt.num_cus() * bpc));
     Workspace ws;
     if ((rc = rt.workspace(stream, (size_t)gx * (size_t)(n * kd), ws, g_err)))
         return rc;
