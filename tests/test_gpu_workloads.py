@@ -59,7 +59,7 @@ def test_workload_small(name, scale):
 
 @pytest.mark.parametrize("name", ["cell", "magg", "row_dense", "row_csr", "outer"])
 def test_workload_full_size(name):
-    """The BASELINE sizes, launched exactly as the benchmark launches them; the
+    """The benchmark sizes, launched exactly as the benchmark launches them; the
     oracle computes the full result (a few seconds per workload on the host)."""
     print("full-size parity:", name, flush=True)
     w = W.make_workload(name, 1.0)
