@@ -232,12 +232,21 @@ def row_csr(expr, x: ops.Csr, sides, agg):
     at the stored positions and may only be consumed by an operator that makes
     the result zero-preserving again (e.g. multiply with X).  Programs that are
     not sparse-safe raise ValueError.
-    Returns: none -> nnz-vector on X's pattern (V) or m (S); row -> m;
-    col / col_t -> n; full -> 1.
+    Products with an n x k right-hand side (vectMatMult over the stored cells of a
+    row) give per-row k-vectors ("K", m x k); "outerk" (vectOuterMultAdd with the
+    column aggregate) sums row (x) k-vector products into n x k.  Both need a
+    zero-preserving row-vector operand.
+    Returns: none -> nnz-vector on X's pattern (V), m (S) or m x k (K); row -> m;
+    col / col_t -> n (V), k (K) or n x k (outerk); full -> 1.
     """
     m, n = x.shape
     rows = ops.csr_row_index(x)
-    st = []   # ("V", nnz-array, zero_preserving) | ("S", array (m,) or 0-d)
+    st = []   # ("V", nnz-array, zero_preserving) | ("S", array (m,) or 0-d) | ("K", m x k) | ("M", n x k)
+    outer = None
+
+    def col1(k, a):        # per-row scalar next to a k-vector: (m,) -> (m, 1)
+        a = np.asarray(a, dtype=np.float64)
+        return a.reshape(m, 1) if (k == "S" and a.ndim == 1) else a
 
     def expand(k, a):      # per-row scalar -> per stored cell
         a = np.asarray(a, dtype=np.float64)
@@ -245,6 +254,8 @@ def row_csr(expr, x: ops.Csr, sides, agg):
 
     for tok in expr:
         name = tok[0]
+        if outer is not None:
+            raise ValueError("outerk must be the last token")
         if name == "main":
             st.append(("V", x.vals, True))
         elif name == "side":
@@ -261,12 +272,20 @@ def row_csr(expr, x: ops.Csr, sides, agg):
                 st.append(("S", a.reshape(m), None))
             elif kind == "scalar":
                 st.append(("S", a.reshape(()), None))
+            elif kind == "rhs":
+                assert a.ndim == 2 and a.shape[0] == n
+                st.append(("M", a, None))
+            elif kind == "kvec":
+                assert a.ndim == 2 and a.shape[0] == m
+                st.append(("K", a, None))
             else:
                 raise ValueError(kind)
         elif name == "const":
             st.append(("S", np.float64(tok[1]), None))
         elif name in ops.UNARY_NAMES:
             k, a, z = st.pop()
+            if k == "M":
+                raise ValueError("a right-hand side can only be consumed by matmult")
             zz = (z and name in _ZERO_PRESERVING_UNARY) if k == "V" else None
             st.append((k, ops.ew_unary(name, a), zz))
         elif name in ops.BINARY_NAMES:
@@ -274,6 +293,11 @@ def row_csr(expr, x: ops.Csr, sides, agg):
             ka, a, za = st.pop()
             if ka == "S" and kb == "S":
                 st.append(("S", ops.ew_binary(name, a, b), None))
+                continue
+            if "M" in (ka, kb) or {ka, kb} == {"V", "K"}:
+                raise ValueError("operands of %r do not conform" % name)
+            if "K" in (ka, kb):
+                st.append(("K", ops.ew_binary(name, col1(ka, a), col1(kb, b)), None))
                 continue
             if name == "mul":
                 z = bool(za) or bool(zb)
@@ -288,21 +312,60 @@ def row_csr(expr, x: ops.Csr, sides, agg):
             if name == "dot":
                 kb, b, zb = st.pop()
                 ka, a, za = st.pop()
+                if ka == "K" and kb == "K":
+                    st.append(("S", ops.row_sums(ops.ew_binary("mul", a, b)), None))
+                    continue
                 if ka != "V" or kb != "V":
-                    raise ValueError("dot needs two row vectors")
+                    raise ValueError("dot needs two row vectors or two k-vectors")
                 a, z, k = ops.ew_binary("mul", a, b), bool(za) or bool(zb), "V"
             else:
                 k, a, z = st.pop()
+                if k == "K":
+                    st.append(("S", ops.row_sums(np.array(a, dtype=np.float64)), None))
+                    continue
             if k != "V":
                 raise ValueError("rowsum of a scalar")
             if not z:
                 raise ValueError("not sparse-safe: row aggregate of a dense-valued vector")
             st.append(("S", ops.csr_row_sums(x, a), None))
+        elif name == "matmult":
+            kb, b, _ = st.pop()
+            ka, a, za = st.pop()
+            if ka != "V" or kb != "M":
+                raise ValueError("matmult needs a row vector and a right-hand side")
+            if not za:
+                raise ValueError("not sparse-safe: product of a dense-valued vector with a right-hand side")
+            st.append(("K", ops.csr_matmul_dense(x, np.array(np.broadcast_to(a, x.vals.shape)), b), None))
+        elif name == "outerk":
+            kb, b, _ = st.pop()
+            ka, a, za = st.pop()
+            if ka != "V" or kb != "K":
+                raise ValueError("outerk needs a row vector and a k-vector")
+            if not za:
+                raise ValueError("not sparse-safe: outer product of a dense-valued vector")
+            outer = (np.array(np.broadcast_to(a, x.vals.shape)), np.array(b, dtype=np.float64))
         else:
             raise ValueError("token %r is not valid in a Row expression" % (tok,))
+    if outer is not None:
+        if st:
+            raise ValueError("expression leaves values on the stack")
+        if agg not in ("col", "col_t"):
+            raise ValueError("a row (x) k-vector result needs the column aggregate")
+        return ops.csr_t_matmul_dense(x, outer[0], outer[1])
     if len(st) != 1:
         raise ValueError("expression leaves %d values on the stack" % len(st))
     kind, r, z = st[0]
+    if kind == "M":
+        raise ValueError("a right-hand side is not a result")
+    if kind == "K":
+        r = np.array(r, dtype=np.float64)
+        if agg == "none":
+            return r
+        if agg in ("col", "col_t"):
+            return ops.col_sums(r)
+        if agg == "full":
+            return np.array([ops.sum_full(r)])
+        raise ValueError("aggregation %r is not defined for a k-vector result" % (agg,))
     if kind == "S":
         per_row = np.array(np.broadcast_to(r, (m,)), dtype=np.float64)
         if agg == "none":

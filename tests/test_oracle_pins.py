@@ -462,3 +462,44 @@ def test_row_matrix_rhs_plans_numpy_interp_and_reductions():
             unfused.row_dense(bad, x, sides, "col_t")
     with pytest.raises(ValueError):
         unfused.row_dense(TXXV, x, sides, "full")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_row_csr_matrix_rhs_equals_dense_semantics_scipy_and_interp(seed):
+    """Row bodies with a right-hand side over a CSR main input (vectMatMult / vectOuterMultAdd over the
+    stored cells of a row): the same values as the dense evaluator on the densified matrix, as scipy's
+    sparse products, and as the per-row interpreter; empty rows and columns give exact zeros."""
+    import scipy.sparse as sp
+    r = _rng(300 + seed)
+    m, n, k = [(40, 13, 3), (7, 50, 1), (64, 9, 5), (25, 25, 16)][seed]
+    rp, ci, va = W.csr_bernoulli(m, n, [0.2, 0.1, 0.5, 0.05][seed], 300 + seed)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    xd = ops.csr_to_dense(x)
+    xs = sp.csr_matrix((va, ci, rp), shape=(m, n))
+    v, p = r.normal(size=(n, k)), r.uniform(size=(m, k))
+    sides = [("rhs", v), ("kvec", p)]
+    got = unfused.row_csr(TXXV, x, sides, "col_t")
+    np.testing.assert_allclose(got, (xs.T @ (xs @ v)), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(got, unfused.row_dense(TXXV, xd, sides, "col_t"), rtol=1e-13, atol=1e-14)
+    q = p * (xs @ v)
+    np.testing.assert_allclose(unfused.row_csr(MLOGREG, x, sides, "col_t"), xs.T @ (q - p * q.sum(1, keepdims=True)),
+                               rtol=1e-11, atol=1e-12)
+    for expr in (TXXV, MLOGREG):
+        np.testing.assert_allclose(unfused.row_csr(expr, x, sides, "col_t"),
+                                   interp.row_sparse(expr, rp, ci, va, (m, n), sides, "col_t"), rtol=1e-11, atol=1e-12)
+    xv = [("main",), ("side", 0), ("matmult",)]
+    np.testing.assert_allclose(unfused.row_csr(xv, x, sides, "none"), xs @ v, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(unfused.row_csr(xv, x, sides, "col"), (xs @ v).sum(0), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(unfused.row_csr(xv, x, sides, "full"), [(xs @ v).sum()], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(unfused.row_csr(MLOG_Q + [("rowsum",)], x, sides, "none"), q.sum(1), rtol=1e-12, atol=1e-13)
+    # rows without stored cells: X V is exactly zero there; columns without stored cells: zero rows of t(X)(XV)
+    empty_rows = np.diff(rp) == 0
+    assert not unfused.row_csr(xv, x, sides, "none")[empty_rows].any()
+    empty_cols = np.bincount(ci, minlength=n) == 0
+    assert not got[empty_cols].any()
+    # not sparse-safe: the row-vector operand must be zero where X has no stored cell
+    for bad in ([("side", 2), ("side", 0), ("matmult",)],                              # dense row vector times V
+                [("main",), ("const", 1.0), ("add",), ("side", 0), ("matmult",)],      # (X + 1) V
+                [("side", 2), ("main",), ("side", 0), ("matmult",), ("outerk",)]):     # t(dense) (X V)
+        with pytest.raises(ValueError):
+            unfused.row_csr(bad, x, sides + [("rowvec", np.ones(n))], "col_t")
