@@ -202,10 +202,12 @@ int fuse_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
  *                   fp64 matrix units.
  * For CSR input the body must be sparse-safe (Sec. 2.2 "Template Types": a
  * sparse-safe template binds only to the non-zeros): every vector that is
- * aggregated or returned must be zero wherever X has no stored cell (products
- * with X, zero-preserving unaries, sums of such); otherwise FUSE_EDESC.
+ * aggregated, multiplied with a right-hand side or returned must be zero
+ * wherever X has no stored cell (products with X, zero-preserving unaries,
+ * sums of such); otherwise FUSE_EDESC.  MATMULT / OUTERK then run over the
+ * stored cells of a row.
  * With CSR input and COL / COL_T the order in which a block's rows are added
- * to a column sum is not fixed (shared-memory atomics up to 7488 columns, fp64
+ * to a column sum is not fixed (shared-memory atomics while the sums fit in LDS, about 18000 columns; fp64
  * atomics on the zeroed output beyond); all else is deterministic.
  * Limits of this build: bodies with ROWSUM / DOT need cols <= 32768 for dense
  * input, bodies with k-vectors cols <= 2048 (FUSE_EUNSUPPORTED beyond).

@@ -77,9 +77,8 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
                 nd.arg = tk.arg;
                 const int kind = sides[tk.arg].kind;
                 if (kind == FUSE_SIDE_RHS || kind == FUSE_SIDE_KVEC) {
-                    if (t != Tmpl::ROW_DENSE)
-                        return fail(err, at + "right-hand-side and k-vector side inputs are only valid in a "
-                                              "Row body over a dense main input");
+                    if (!row)
+                        return fail(err, at + "right-hand-side and k-vector side inputs are only valid in a Row body");
                     const int kd = (int)sides[tk.arg].m.cols;
                     if (kd < 1 || kd > FUSE_MAX_K)
                         return fail(err, at + "k (columns of the side input) must be in [1, " +
@@ -167,8 +166,8 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
                     nd.level = lvl + 1;
                 }
             } else if (tk.op == FUSE_OP_MATMULT) {
-                if (t != Tmpl::ROW_DENSE)
-                    return fail(err, at + "MATMULT is only valid in a Row body over a dense main input");
+                if (!row)
+                    return fail(err, at + "MATMULT is only valid in a Row body");
                 if (st.size() < 2)
                     return fail(err, at + "MATMULT needs a row vector and a right-hand side");
                 nd.b = st.back();
@@ -178,12 +177,15 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
                 const Node &a = prog.nodes[nd.a], &b = prog.nodes[nd.b];
                 if (a.kind != KIND_V || b.kind != KIND_M)
                     return fail(err, at + "MATMULT needs a row vector and a right-hand side");
+                if (t == Tmpl::ROW_CSR && !a.zp)
+                    return fail(err, at + "not sparse-safe: product of a vector that is not zero where the main "
+                                          "input has no stored cell");
                 nd.kind = KIND_K;
                 nd.arg = b.arg;             // the right-hand side's side index
                 nd.level = a.level + 1;
             } else if (tk.op == FUSE_OP_OUTERK) {
-                if (t != Tmpl::ROW_DENSE)
-                    return fail(err, at + "OUTERK is only valid in a Row body over a dense main input");
+                if (!row)
+                    return fail(err, at + "OUTERK is only valid in a Row body");
                 if (st.size() < 2)
                     return fail(err, at + "OUTERK needs a row vector and a k-vector");
                 nd.b = st.back();
@@ -193,6 +195,9 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
                 const Node &a = prog.nodes[nd.a], &b = prog.nodes[nd.b];
                 if (a.kind != KIND_V || b.kind != KIND_K)
                     return fail(err, at + "OUTERK needs a row vector and a k-vector");
+                if (t == Tmpl::ROW_CSR && !a.zp)
+                    return fail(err, at + "not sparse-safe: outer product of a vector that is not zero where the "
+                                          "main input has no stored cell");
                 nd.kind = KIND_VK;
                 nd.level = a.level > b.level ? a.level : b.level;
             } else {

@@ -678,8 +678,15 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     Runtime &rt = Runtime::get();
     const int64_t m = X->rows, n = X->cols;
     const int ac = agg_code(agg);
-    if (!prog.result_vec && (ac == 2 || ac == 3))
+    const int rk = prog.result_kind;
+    const int kd = prog.kdim;
+    if (rk == KIND_S && (ac == 2 || ac == 3))
         return fail(FUSE_EDESC, "row / column aggregation needs a row-vector result");
+    if (rk == KIND_K && ac == 2)
+        return fail(FUSE_EDESC, "a k-vector result has the variants no_agg, col_agg and full_agg");
+    if (rk == KIND_VK && ac != 3)
+        return fail(FUSE_EDESC, "an OUTERK result needs FUSE_AGG_COL / FUSE_AGG_COL_T");
+    const int64_t nacck = rk == KIND_VK ? kd : 1;           // running sums per column
 
     // lanes per row from the mean row length
     // lanes per row (G) and register-resident cells per lane (C): C*G covers rows of
@@ -709,24 +716,29 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     bool need_rid = prog.nred > 0 || ac == 2 || !prog.result_vec;
     for (int k = 0; k < nsides; ++k)
         need_rid |= prog.side_used[k] && (sides[k].kind == FUSE_SIDE_MATRIX || sides[k].kind == FUSE_SIDE_COLVEC);
-    const bool streaming = stream_mode == 1 || (stream_mode == 2 && (G * C <= 8 || !need_rid));
+    // (bodies with k-vectors run in the lane-group form only)
+    const bool streaming = kd == 0 && (stream_mode == 1 || (stream_mode == 2 && (G * C <= 8 || !need_rid)));
 
     // LDS plan: the column accumulator first, then staged row-vector sides if they fit
     int nrv = 0;
     for (int k = 0; k < nsides; ++k)
         nrv += prog.side_used[k] && sides[k].kind == FUSE_SIDE_ROWVEC;
-    const int64_t lds_budget = 64000;
-    // column sums: a per-block LDS vector while it fits (cols <= 7488), else fp64 atomics on the output
-    const bool cols_global = ac == 3 && n * 8 > lds_budget - 4096;
-    const bool cols_lds = ac == 3 && !cols_global;
-    const bool stage_rv = nrv > 0 && ((cols_lds ? n : 0) + (int64_t)nrv * n) * 8 <= lds_budget - 1024;
+    // one block per CU: most of the 160 KB of LDS can go to the column sums and the staged row vectors
+    // (the streaming form keeps per-wave histograms and row totals there as well)
+    const int64_t lds_budget = streaming ? 96 * 1024 : 144 * 1024;
+    // column sums: a per-block LDS vector while it fits, else fp64 atomics on the output
+    const bool col_acc = ac == 3 && rk != KIND_K;          // per-column running sums (k per column for OUTERK)
+    const bool cols_global = col_acc && n * nacck * 8 > lds_budget - 4096;
+    const bool cols_lds = col_acc && !cols_global;
+    const bool stage_rv = nrv > 0 && ((cols_lds ? n * nacck : 0) + (int64_t)nrv * n) * 8 <= lds_budget - 1024;
     const int64_t npad = (cols_lds || stage_rv) ? std::max<int64_t>(n, 1) : 1;
+    const int64_t naccpad = cols_lds ? std::max<int64_t>(n * nacck, 1) : 1;
 
     const int nt = env_int("FUSE_CSR_NT", streaming ? 1 : 0);
     const std::string key = std::string("rowcsr|") + prog.key + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(ac) + (streaming ? "|stream" + std::to_string(SC) + "r" + std::to_string(need_rid)
                                                             : "|g" + std::to_string(G) + "c" + std::to_string(C) + "r" + std::to_string(RS)) + "b" +
-                            std::to_string(BLOCK) + "p" + std::to_string(npad) + "s" + std::to_string(stage_rv) + (cols_global ? "G" : "") +
+                            std::to_string(BLOCK) + "p" + std::to_string(npad) + "a" + std::to_string(naccpad) + "s" + std::to_string(stage_rv) + (cols_global ? "G" : "") +
                             "w" + std::to_string(X->rowptr_is64 != 0) + std::to_string(m < (1LL << 30)) + "nt" +
                             std::to_string(nt);
     std::shared_ptr<Plan> plan;
@@ -743,7 +755,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
              "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_AGG " + std::to_string(ac) +
              "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) + "\n#define FUSE_ROW32 " +
              std::to_string(m < (1LL << 30)) + "\n#define FUSE_NPAD " +
-             std::to_string(npad) + "\n#define FUSE_STAGE_RV " + std::to_string(stage_rv) +
+             std::to_string(npad) + "\n#define FUSE_NACCPAD " + std::to_string(naccpad) + "\n#define FUSE_STAGE_RV " + std::to_string(stage_rv) +
              "\n#define FUSE_NRV " + std::to_string(std::max(nrv, 1)) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_row_body(prog);
@@ -760,8 +772,12 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     Plan::Loaded fn;
     if ((rc = rt.load(*plan, fn, g_err)))
         return rc;
-    const int64_t out_count = ac == 0 ? (prog.result_vec ? X->nnz : m)
-                                      : ac == 1 ? (int64_t)prog.roots.size() : ac == 2 ? m : n;
+    int64_t out_count = ac == 0 ? (prog.result_vec ? X->nnz : m)
+                                : ac == 1 ? (int64_t)prog.roots.size() : ac == 2 ? m : n;
+    if (rk == KIND_K)
+        out_count = ac == 0 ? m * kd : ac == 3 ? kd : 1;
+    else if (rk == KIND_VK)
+        out_count = n * kd;
     if (m == 0)
         return zero_fill(fn, out, out_count, stream);
 
@@ -775,8 +791,9 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
         gx = (X->nnz + (int64_t)64 * SC * NW - 1) / ((int64_t)64 * SC * NW);
     gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CSR_BLOCKS_PER_CU", 1)));
     Workspace ws;
-    const size_t need = cols_lds ? (size_t)gx * (size_t)n : (size_t)gx * prog.roots.size();
-    if (cols_global && (rc = zero_fill(fn, out, n, stream)))
+    const size_t need = cols_lds ? (size_t)gx * (size_t)(n * nacck)
+                                 : (size_t)gx * std::max<size_t>(prog.roots.size(), (size_t)std::max(kd, 1));
+    if (cols_global && (rc = zero_fill(fn, out, n * nacck, stream)))
         return rc;
     if ((rc = rt.workspace(stream, need, ws, g_err)))
         return rc;
@@ -802,7 +819,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     if ((rc = rt.launch(fn.main, (unsigned)gx, 1, BLOCK, stream, &A, sizeof A, g_err)))
         return rc;
     if (cols_lds)
-        return run_combine(fn, ws.partials, (int)gx, (int)n, out, stream);
+        return run_combine(fn, ws.partials, (int)gx, (int)(n * nacck), out, stream);
     return 0;
 }
 

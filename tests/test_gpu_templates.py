@@ -383,7 +383,7 @@ def test_row_csr_column_sums_of_wide_matrices(csr_mapping):
     atomics on the output.  Counts are exact, t(X)(Xv) within the usual bar."""
     import paper_1801_00829_amd as F
     from oracle import plans
-    for (m, n, d) in ((3000, 20000, 0.0005), (500, 100001, 0.0002), (40, 9000, 0.3)):
+    for (m, n, d) in ((3000, 20000, 0.0005), (500, 100001, 0.0002), (40, 19000, 0.2)):
         rp, ci, va = W.csr_bernoulli(m, n, d, 4242)
         print("wide csr", (m, n), "nnz", int(rp[-1]), csr_mapping, flush=True)
         xd = dev_csr(rp, ci, np.ones_like(va), (m, n))
@@ -688,6 +688,42 @@ def test_row_matrix_rhs_chain_and_mlogreg_core(shape, rhs_form):
     assert_close(host(F.fuse_row(MLOG_Q + [("rowsum",)], xd, sd, "none")),
                  unfused.row_dense(MLOG_Q + [("rowsum",)], x, [("rhs", v), ("kvec", p)], "none"),
                  scale=(absx @ absv).sum(1).max(), what="rowSums(Q)")
+
+
+@pytest.mark.parametrize("k", [1, 3, 10, 16])
+def test_row_csr_matrix_rhs_on_all_patterns(k):
+    """t(X)(XV), the MLogreg core and k-vector results over a CSR main input: products over the stored
+    cells of a row (vectMatMult), outer products summed into n x k (vectOuterMultAdd)."""
+    import paper_1801_00829_amd as F
+    xv = [("main",), ("side", 0), ("matmult",)]
+    for name, (rp, ci, va), shape in _csr_cases():
+        m, n = shape
+        rng = np.random.default_rng(91)
+        v, p = rng.normal(size=(n, k)), rng.uniform(size=(m, k))
+        x = ops.make_csr(rp, ci, va, shape)
+        xd, sd = dev_csr(rp, ci, va, shape), [("rhs", to_dev(v)), ("kvec", to_dev(p))]
+        hs = [("rhs", v), ("kvec", p)]
+        print("row csr matrix rhs", name, shape, "k", k, flush=True)
+        ax = ops.make_csr(rp, ci, np.abs(va), shape)
+        absq = ops.csr_matmul_dense(ax, ax.vals, np.abs(v)) if va.size else np.zeros((m, k))
+        scale = max(ops.csr_t_matmul_dense(ax, ax.vals, absq).max(initial=0.0), 1e-300)
+        for expr, fac in ((TXXV, 1.0), (MLOGREG, 2.0 * k)):
+            got = host(F.fuse_row(expr, xd, sd, "col_t")).reshape(n, k)
+            ref = unfused.row_csr(expr, x, hs, "col_t")
+            assert_close(got, ref, scale=fac * scale, what="csr %s" % ("t(X)(XV)" if expr is TXXV else "mlogreg core"))
+            assert not got[np.bincount(ci, minlength=n) == 0].any()          # columns without stored cells
+        s1 = max(absq.max(initial=0.0), 1e-300)
+        got = host(F.fuse_row(xv, xd, sd, "none")).reshape(m, k)
+        assert_close(got, unfused.row_csr(xv, x, hs, "none"), scale=s1, what="csr X V")
+        assert not got[np.diff(rp) == 0].any()                               # rows without stored cells
+        assert_close(host(F.fuse_row(xv, xd, sd, "col")), unfused.row_csr(xv, x, hs, "col"),
+                     scale=max(absq.sum(0).max(initial=0.0), 1e-300), what="csr colSums(X V)")
+        assert_close(host(F.fuse_row(xv, xd, sd, "full")), unfused.row_csr(xv, x, hs, "full"),
+                     scale=max(absq.sum(), 1e-300), what="csr sum(X V)")
+        # a body that also has a value on rows without stored cells: rowSums(P * (X V)) + rowSums(P)
+        e2 = MLOG_Q + [("rowsum",), ("side", 1), ("rowsum",), ("add",)]
+        assert_close(host(F.fuse_row(e2, xd, sd, "none")), unfused.row_csr(e2, x, hs, "none"),
+                     scale=max(absq.sum(1).max(initial=0.0) + k, 1.0), what="csr rowSums(Q) + rowSums(P)")
 
 
 def test_row_matrix_rhs_strided_sides_and_limits(rhs_form):

@@ -216,9 +216,17 @@ def test_row_matrix_rhs_type_checking(F):
     with pytest.raises(F.FuseError) as e:                                 # register budget: ceil(n/2048)*2*k <= 48
         F.prepare_row(txxv, (100, 6000), [("rhs", (6000, 16))], "col_t")
     assert e.value.code == -7
-    with pytest.raises(F.FuseError) as e:                                 # CSR main input
-        F.prepare_row(xv, (1000, 100), [("rhs", (100, 4))], "none", nnz=500)
-    assert e.value.code in (-3, -7)
+    # CSR main input: the products run over the stored cells of a row; the row-vector operand must be sparse-safe
+    F.prepare_row(xv, (1000, 100), [("rhs", (100, 4))], "none", nnz=500)
+    F.prepare_row(txxv, (1000, 100), [("rhs", (100, 4))], "col_t", nnz=500)
+    assert "#define FUSE_RESULT_KIND 4" in F.last_source() and "fuse_csr_rhs" in F.last_source()
+    F.prepare_row(core, (1000, 100), [("rhs", (100, 4)), ("kvec", (1000, 4))], "col_t", nnz=500)
+    for bad in ([("side", 1), ("side", 0), ("matmult",)],                                   # dense row vector times V
+                [("main",), ("const", 1.0), ("add",), ("side", 0), ("matmult",)],           # (X + 1) V
+                [("side", 1), ("main",), ("side", 0), ("matmult",), ("outerk",)]):          # t(dense) (X V)
+        with pytest.raises(F.FuseError) as e:
+            F.prepare_row(bad, (1000, 100), [("rhs", (100, 4)), ("rowvec", None)], "col_t", nnz=500)
+        assert e.value.code == -3 and "sparse-safe" in str(e.value)
 
 
 def test_every_operator_compiles(F):
