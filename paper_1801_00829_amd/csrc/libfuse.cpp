@@ -471,7 +471,7 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     const int BLOCK = WPR > 1 ? std::max(128, 64 * WPR) : 256;
     if (WPR > 1 && BLOCK != 64 * WPR)
         WPR = BLOCK / 64;          // at least two waves per block
-    if (WPR > 1)
+    if (WPR > 1)          // (more rows in flight per block were tried: no gain at k = 4, spills at k = 10)
         RS = 1;
 
     const std::string key = std::string("rowdense|") + pkey + "|rk" + std::to_string(rk) + "|" + side_key(sides, nsides) + "|agg" +
