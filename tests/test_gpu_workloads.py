@@ -74,3 +74,29 @@ def test_workload_full_size(name):
         assert np.array_equal(_run(w), got)
     else:
         assert_close(_run(w), got, tol=1e-13, what="row_csr rerun")
+
+
+def test_calls_on_two_streams_keep_their_own_workspaces():
+    """Every (device, stream) pair has its own block partials and arrival counter: operators that
+    overlap on two streams (default priorities) must not disturb each other's aggregates."""
+    import torch
+    import paper_1801_00829_amd as F
+    from oracle import plans
+    rng = np.random.default_rng(17)
+    xs = [rng.uniform(size=(700, 900)) for _ in range(2)]
+    ys = [rng.uniform(size=(700, 900)) for _ in range(2)]
+    zs = [rng.uniform(size=(700, 900)) for _ in range(2)]
+    expr = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+    refs = [plans.cell_sum_xyz(xs[i], ys[i], zs[i])[0] for i in range(2)]
+    dev = [tuple(torch.from_numpy(a).cuda() for a in (xs[i], ys[i], zs[i])) for i in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [[torch.empty(1, dtype=torch.float64, device="cuda") for _ in range(12)] for _ in range(2)]
+    torch.cuda.synchronize()
+    for rep in range(12):
+        for i in range(2):
+            x, y, z = dev[i]
+            F.fuse_cell(expr, x, [("matrix", y), ("matrix", z)], "full", out=outs[i][rep], stream=streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        for rep in range(12):
+            assert abs(float(outs[i][rep].cpu()[0]) - refs[i]) <= 1e-10 * abs(refs[i]), (i, rep)
