@@ -710,7 +710,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     // for lane groups, 10 per row 264 against 234, 100 per row 344 against 267.
     // FUSE_CSR_STREAM: 0 never, 1 always, 2 by this rule.
     const int stream_mode = env_int("FUSE_CSR_STREAM", 2);
-    const int SC = 4;                                    // cells per lane of the streaming skeleton
+    const int SC = 4;                                    // cells per lane of the streaming skeleton (8: slower, 442 us on config 4)
     // bodies that never look at the row (no row aggregate, no per-row side, one value per cell)
     // run the streaming skeleton's flat form over the cell arrays, whatever the row lengths
     bool need_rid = prog.nred > 0 || ac == 2 || !prog.result_vec;
