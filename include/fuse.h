@@ -73,7 +73,7 @@ typedef enum {
     FUSE_SIDE_COLVEC = 1,   /* `rows` values, value at rix  (data[rix * ld])          */
     FUSE_SIDE_ROWVEC = 2,   /* `cols` values, value at cix  (data[cix], contiguous)   */
     FUSE_SIDE_SCALAR = 3,   /* host scalar in `scalar`; passed as a kernel argument   */
-    /* Row bodies over a dense main input only (Sec. 2.2 Row listing, vectMatMult / getVector): */
+    /* Row bodies only (Sec. 2.2 Row listing, vectMatMult / getVector): */
     FUSE_SIDE_RHS = 4,      /* cols(X) x k right-hand side of FUSE_OP_MATMULT, 1 <= k <= 16 */
     FUSE_SIDE_KVEC = 5      /* rows(X) x k: row rix is a k-vector (data[rix * ld + j])       */
 } fuse_side_kind;
@@ -125,7 +125,7 @@ typedef enum {
     FUSE_OP_ROWSUM = 48,    /* sum over the columns of a row vector, or over the
                                entries of a k-vector                  (vectSum)        */
     FUSE_OP_DOT = 49,       /* inner product of two row vectors / two k-vectors (dotProduct) */
-    /* Row template over a dense main input only */
+    /* Row template only (over a CSR main input: the products run over the stored cells) */
     FUSE_OP_MATMULT = 50,   /* pops a RHS side, then a row vector; pushes the k-vector
                                row %*% RHS                             (vectMatMult)    */
     FUSE_OP_OUTERK = 51     /* last token: pops a k-vector, then a row vector; the result is
@@ -190,7 +190,7 @@ int fuse_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
  *                   (Xs); ROW -> m row sums; COL / COL_T -> n column sums
  *                   (t(X) %*% q is the body `X_i * q_i` with COL_T); FULL -> 1.
  *   scalar result:  NONE -> m values; FULL -> 1; others FUSE_EDESC.
- *   k-vector result (dense input; products with a FUSE_SIDE_RHS, FUSE_SIDE_KVEC sides;
+ *   k-vector result (products with a FUSE_SIDE_RHS, FUSE_SIDE_KVEC sides;
  *                   element-wise operators work per component, scalars broadcast):
  *                   NONE -> m x k; COL / COL_T -> k sums over the rows; FULL -> 1.
  *   OUTERK result:  COL / COL_T -> out is n x k, contiguous: sum over the rows of
@@ -254,6 +254,17 @@ int fuse_prepare_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr
                      const fuse_side *sides, int nsides, int agg);
 int fuse_prepare_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U,
                        const fuse_dense *V, const fuse_side *sides, int nsides, int agg);
+
+/* Structure check of a CSR matrix, on the device (the template calls themselves trust the
+ * format they are given: offsets or column indices that point outside the arrays make them
+ * read outside the arrays).  Verifies rowptr[0] == 0, rowptr[rows] == nnz, non-decreasing
+ * offsets inside [0, nnz], every column index in [0, cols) and strictly ascending column
+ * indices within each row (sorted, no duplicates); no cell is read before its row's offsets
+ * have passed.  The values are not looked at.  Enqueues one kernel on `stream` and WAITS for
+ * the stream (the only call here that synchronises; it also allocates and frees 32 bytes of
+ * device memory).  FUSE_OK, or FUSE_ESHAPE with fuse_last_error() naming the violation and
+ * the first row that shows it; FUSE_EINVAL for NULL arrays. */
+int fuse_check_csr(const fuse_csr *X, void *stream);
 
 /* Message of the calling thread's last failed call ("" if none).  The pointer
  * stays valid until that thread's next libfuse call. */

@@ -66,7 +66,8 @@ def load():
     lib.fuse_prepare_magg.argtypes = [P(Expr), ci, P(Dense), P(Side), ci]
     lib.fuse_prepare_row.argtypes = [P(Expr), P(Dense), P(CsrDesc), P(Side), ci, ci]
     lib.fuse_prepare_outer.argtypes = [P(Expr), P(CsrDesc), P(Dense), P(Dense), P(Side), ci, ci]
-    for f in (lib.fuse_cell_csr, lib.fuse_magg_csr, lib.fuse_prepare_cell_csr, lib.fuse_prepare_magg_csr,
+    lib.fuse_check_csr.argtypes = [P(CsrDesc), vp]
+    for f in (lib.fuse_check_csr, lib.fuse_cell_csr, lib.fuse_magg_csr, lib.fuse_prepare_cell_csr, lib.fuse_prepare_magg_csr,
               lib.fuse_cell, lib.fuse_magg, lib.fuse_row, lib.fuse_outer, lib.fuse_prepare_cell,
               lib.fuse_prepare_magg, lib.fuse_prepare_row, lib.fuse_prepare_outer):
         f.restype = ci

@@ -312,6 +312,13 @@ def fuse_outer(expr, X, U, V, sides=(), agg="full", out=None, stream=None):
     return out
 
 
+def check_csr(X, stream=None):
+    """C: fuse_check_csr.  Raises FuseError (FUSE_ESHAPE) if the CSR structure is malformed; waits for the stream."""
+    lib = L.load()
+    xs = _csr(X)
+    _check(lib.fuse_check_csr(ctypes.byref(xs), _stream(stream)))
+
+
 # ----------------------------------------------------- compile-only (no device needed) ---
 
 def prepare_cell(expr, shape, sides=(), agg="full", ld=None):

@@ -8,6 +8,8 @@
 #include <cstring>
 #include <memory>
 #include <mutex>
+#include <new>
+#include <stdexcept>
 #include <string>
 #include <unordered_map>
 
@@ -213,8 +215,10 @@ int check_csr(const fuse_csr *X, bool need_data)
         return fail(FUSE_EUNSUPPORTED, "X: more than 2^31-1 columns (int32 column indices)");
     if (!X->rowptr_is64 && X->nnz > 2147483647LL)
         return fail(FUSE_EINVAL, "X: nnz does not fit the int32 row offsets");
-    if (X->nnz > X->rows * X->cols && X->rows * X->cols >= 0 && X->cols > 0 && X->rows <= (int64_t)4e18 / X->cols)
-        return fail(FUSE_ESHAPE, "X: nnz exceeds rows * cols");
+    if (X->cols == 0 || X->rows <= (int64_t)4e18 / X->cols) {       // rows * cols representable
+        if (X->nnz > X->rows * X->cols)
+            return fail(FUSE_ESHAPE, "X: nnz exceeds rows * cols");
+    }
     if (need_data && (!X->rowptr || (X->nnz > 0 && (!X->vals || !X->colidx))))
         return fail(FUSE_EINVAL, "X: NULL CSR array");
     return 0;
@@ -1100,6 +1104,54 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     return rt.launch(fn.main, (unsigned)gx, 1, BLOCK, stream, &A, sizeof A, g_err);
 }
 
+int check_csr_device(const fuse_csr *X, void *stream_)
+{
+    g_err.clear();
+    int rc = check_csr(X, true);
+    if (rc)
+        return rc;
+    hipStream_t stream = (hipStream_t)stream_;
+    unsigned long long *dev = nullptr;
+    unsigned long long bad[4] = {~0ull, ~0ull, ~0ull, 0ull};
+    hipError_t e = hipMalloc((void **)&dev, sizeof bad);
+    if (e != hipSuccess)
+        return fail(FUSE_ENOMEM, std::string("fuse_check_csr: ") + hipGetErrorString(e));
+    e = hipMemcpyAsync(dev, bad, sizeof bad, hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess && check_csr_launch(X->rowptr, X->rowptr_is64, X->colidx, X->rows, X->cols, X->nnz, dev, stream))
+        e = hipErrorLaunchFailure;
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(bad, dev, sizeof bad, hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess)
+        e = hipStreamSynchronize(stream);
+    (void)hipFree(dev);
+    if (e != hipSuccess)
+        return fail(FUSE_ERUNTIME, std::string("fuse_check_csr: ") + hipGetErrorString(e));
+    if (bad[3] & 1)
+        return fail(FUSE_ESHAPE, "X: rowptr[0] is not 0");
+    if (bad[0] != ~0ull)
+        return fail(FUSE_ESHAPE, "X: row offsets decrease or leave [0, nnz] at row " + std::to_string(bad[0]));
+    if (bad[3] & 2)
+        return fail(FUSE_ESHAPE, "X: rowptr[rows] differs from nnz");
+    if (bad[1] != ~0ull)
+        return fail(FUSE_ESHAPE, "X: column index outside [0, cols) in row " + std::to_string(bad[1]));
+    if (bad[2] != ~0ull)
+        return fail(FUSE_ESHAPE, "X: column indices not strictly ascending in row " + std::to_string(bad[2]));
+    return 0;
+}
+
+// No C++ exception may cross the C boundary.
+template <typename F>
+int guarded(F f)
+{
+    try {
+        return f();
+    } catch (const std::bad_alloc &) {
+        return fail(FUSE_ENOMEM, "out of host memory");
+    } catch (const std::exception &ex) {
+        return fail(FUSE_ERUNTIME, std::string("internal error: ") + ex.what());
+    }
+}
+
 }  // namespace
 
 // =============================================================================
@@ -1108,69 +1160,74 @@ extern "C" {
 int fuse_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_side *sides, int nsides, int agg,
               double *out, void *stream)
 {
-    return cell_impl(expr, 1, X, sides, nsides, agg, out, stream, true, false);
+    return guarded([&] { return cell_impl(expr, 1, X, sides, nsides, agg, out, stream, true, false); });
 }
 
 int fuse_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides, int nsides,
               double *out_k, void *stream)
 {
-    return cell_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, out_k, stream, true, true);
+    return guarded([&] { return cell_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, out_k, stream, true, true); });
 }
 
 int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, const fuse_side *sides,
              int nsides, int agg, double *out, void *stream)
 {
-    return row_impl(expr, Xd, Xs, sides, nsides, agg, out, stream, true);
+    return guarded([&] { return row_impl(expr, Xd, Xs, sides, nsides, agg, out, stream, true); });
 }
 
 int fuse_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
                const fuse_side *sides, int nsides, int agg, double *out, void *stream)
 {
-    return outer_impl(expr, X, U, V, sides, nsides, agg, out, stream, true);
+    return guarded([&] { return outer_impl(expr, X, U, V, sides, nsides, agg, out, stream, true); });
 }
 
 int fuse_cell_csr(const fuse_expr *expr, const fuse_csr *X, const fuse_side *sides, int nsides, int agg,
                   double *out, void *stream)
 {
-    return cell_csr_impl(expr, 1, X, sides, nsides, agg, out, stream, true, false);
+    return guarded([&] { return cell_csr_impl(expr, 1, X, sides, nsides, agg, out, stream, true, false); });
 }
 
 int fuse_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_side *sides, int nsides,
                   double *out_k, void *stream)
 {
-    return cell_csr_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, out_k, stream, true, true);
+    return guarded([&] { return cell_csr_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, out_k, stream, true, true); });
 }
 
 int fuse_prepare_cell_csr(const fuse_expr *expr, const fuse_csr *X, const fuse_side *sides, int nsides, int agg)
 {
-    return cell_csr_impl(expr, 1, X, sides, nsides, agg, nullptr, nullptr, false, false);
+    return guarded([&] { return cell_csr_impl(expr, 1, X, sides, nsides, agg, nullptr, nullptr, false, false); });
 }
 
 int fuse_prepare_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_side *sides, int nsides)
 {
-    return cell_csr_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, nullptr, nullptr, false, true);
+    return guarded([&] { return cell_csr_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, nullptr, nullptr, false, true); });
 }
 
 int fuse_prepare_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_side *sides, int nsides, int agg)
 {
-    return cell_impl(expr, 1, X, sides, nsides, agg, nullptr, nullptr, false, false);
+    return guarded([&] { return cell_impl(expr, 1, X, sides, nsides, agg, nullptr, nullptr, false, false); });
 }
 
 int fuse_prepare_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides, int nsides)
 {
-    return cell_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, nullptr, nullptr, false, true);
+    return guarded([&] { return cell_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, nullptr, nullptr, false, true); });
 }
 
 int fuse_prepare_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, const fuse_side *sides,
                      int nsides, int agg)
 {
-    return row_impl(expr, Xd, Xs, sides, nsides, agg, nullptr, nullptr, false);
+    return guarded([&] { return row_impl(expr, Xd, Xs, sides, nsides, agg, nullptr, nullptr, false); });
 }
 
 int fuse_prepare_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
                        const fuse_side *sides, int nsides, int agg)
 {
-    return outer_impl(expr, X, U, V, sides, nsides, agg, nullptr, nullptr, false);
+    return guarded([&] { return outer_impl(expr, X, U, V, sides, nsides, agg, nullptr, nullptr, false); });
+}
+
+int fuse_check_csr(const fuse_csr *X, void *stream)
+{
+    return guarded([&] { return check_csr_device(X, stream); });
 }
 
 const char *fuse_last_error(void) { return g_err.c_str(); }

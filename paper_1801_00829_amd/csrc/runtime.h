@@ -99,4 +99,9 @@ private:
     double compile_ms_ = 0.0;
 };
 
+// Launches the CSR structure check (check.hip); `bad` points to four device words, the first
+// three preset to all ones and the last to zero.  0 on success.
+int check_csr_launch(const void *rowptr, int rowptr_is64, const int *colidx, long long rows, long long cols,
+                     long long nnz, unsigned long long *bad, hipStream_t stream);
+
 }  // namespace fuse

@@ -350,6 +350,51 @@ def test_row_csr_index_handling_is_bit_exact(csr_mapping):
         assert np.array_equal(got, cv[rows] * rv[ci])
 
 
+@pytest.mark.parametrize("rowptr64", [False, True])
+def test_check_csr_accepts_every_pattern_and_names_each_violation(rowptr64):
+    """The structure check passes all generated patterns and reports each kind of planted
+    damage with the row that shows it (the check itself never reads outside the arrays)."""
+    import paper_1801_00829_amd as F
+    for name, (rp, ci, va), shape in _csr_cases():
+        print("check csr ok", name, flush=True)
+        F.check_csr(dev_csr(rp, ci, va, shape, rowptr64))
+    rp, ci, va = W.csr_fixed_per_row(120, 90, 6, 108)
+    shape, nnz = (120, 90), int(rp[-1])
+
+    def expect(what, rp_, ci_, text, nnz_=None):
+        print("check csr bad:", what, flush=True)
+        x = dev_csr(rp_, ci_, va, shape, rowptr64)
+        if nnz_ is not None:          # arrays keep their length; only the declared count differs
+            x = F.Csr(x.rowptr, x.colidx[:nnz_], x.vals[:nnz_], shape)
+        with pytest.raises(F.FuseError) as err:
+            F.check_csr(x)
+        assert err.value.code == -2          # FUSE_ESHAPE
+        assert text in str(err.value), (what, str(err.value))
+
+    r = 37
+    bad = rp.copy(); bad[0] = 1
+    expect("first offset", bad, ci, "rowptr[0] is not 0")
+    bad = rp.copy(); bad[r + 1] = bad[r] - 1
+    expect("decreasing offsets", bad, ci, "at row %d" % r)
+    bad = rp.copy(); bad[r + 1] = nnz + 5
+    expect("offset past the arrays", bad, ci, "at row %d" % r)
+    bad = rp.copy(); bad[-1] = nnz - 2
+    expect("last offset below nnz", bad, ci, "rowptr[rows] differs from nnz")
+    expect("declared nnz below the last offset", rp, ci, "leave [0, nnz] at row %d" % (shape[0] - 1), nnz_=nnz - 3)
+    p = int(rp[r]) + 2
+    bad = ci.copy(); bad[p] = shape[1]
+    expect("column == cols", rp, bad, "outside [0, cols) in row %d" % r)
+    bad = ci.copy(); bad[int(rp[r])] = -1
+    expect("negative column", rp, bad, "outside [0, cols) in row %d" % r)
+    bad = ci.copy(); bad[p], bad[p + 1] = bad[p + 1], bad[p]
+    expect("unsorted columns", rp, bad, "not strictly ascending in row %d" % r)
+    bad = ci.copy(); bad[p + 1] = bad[p]
+    expect("duplicate column", rp, bad, "not strictly ascending in row %d" % r)
+    # the last column of one row may exceed the first of the next: rows are independent
+    bad = ci.copy(); bad[int(rp[r + 1]) - 1] = shape[1] - 1; bad[int(rp[r + 1])] = 0
+    F.check_csr(dev_csr(rp, bad, va, shape, rowptr64))
+
+
 @pytest.mark.parametrize("case", range(12 * MORE))
 def test_row_csr_random_sparse_safe_expressions(case, csr_mapping):
     import paper_1801_00829_amd as F

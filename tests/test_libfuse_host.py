@@ -136,6 +136,15 @@ def test_shape_and_argument_errors(F):
     assert lib.fuse_prepare_outer(ctypes.byref(e), ctypes.byref(L.CsrDesc(None, None, None, 0, 4, 4, 17)),
                                   ctypes.byref(L.Dense(None, 4, 3, 3)), ctypes.byref(L.Dense(None, 4, 3, 3)),
                                   None, 0, 1) == -2
+    # the structure check rejects NULL arrays and impossible counts on the host, before any device call
+    assert lib.fuse_check_csr(None, None) == -1
+    assert lib.fuse_check_csr(ctypes.byref(L.CsrDesc(None, None, None, 0, 4, 4, 3)), None) == -1
+    assert b"NULL CSR array" in lib.fuse_last_error()
+    assert lib.fuse_check_csr(ctypes.byref(L.CsrDesc(None, None, None, 0, 4, 4, 17)), None) == -2
+    # rows * cols beyond int64 must not trip the nnz <= rows * cols test
+    huge = L.CsrDesc(None, None, None, 1, 1 << 40, 1 << 30, 1 << 40)
+    e3, keep3 = F.api._expr([("main",), ("rowsum",)])
+    assert lib.fuse_prepare_row(ctypes.byref(e3), None, ctypes.byref(huge), None, 0, 0) == 0
     # Outer: factor shapes
     ok = L.CsrDesc(None, None, None, 0, 4, 6, 5)
     e2, keep2 = F.api._expr([("main",), ("uvdot",), ("mul",)])
