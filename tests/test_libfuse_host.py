@@ -252,6 +252,38 @@ def test_every_operator_compiles(F):
     F.prepare_outer(expr + [("uvdot",), ("mul",)], (16, 16), 5, 20, [("rowvec", None)], "none")
 
 
+def test_plan_cache_is_thread_safe(F):
+    """Several host threads prepare the same and different operators at once: every call succeeds and equal
+    requests end up on one plan (threads that meet on a new plan may each compile it; one copy is kept)."""
+    import threading
+    F.cache_clear()
+    bodies = [[("main",), ("const", float(c)), ("mul",), ("side", 0), ("add",)] for c in range(3, 7)]
+    errors, names = [], {}
+
+    def work(tid):
+        try:
+            for rep in range(3):
+                for j, body in enumerate(bodies):
+                    F.prepare_cell(body, (64, 32), [("matrix", None)], "full")
+                    names.setdefault(j, set()).add(F.last_kernel())
+                    F.prepare_row([("main",), ("side", 0), ("dot",), ("main",), ("mul",)], (50, 20), [("rowvec", None)],
+                                  "col_t")
+        except Exception as e:            # noqa: BLE001 - reported below
+            errors.append((tid, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(6)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    assert all(len(v) == 1 for v in names.values()), names          # one kernel name per body
+    assert len({next(iter(v)) for v in names.values()}) == len(bodies)
+    hits, misses, _ = F.cache_stats()
+    assert hits + misses == 6 * 3 * len(bodies) * 2
+    assert len(bodies) + 1 <= misses <= 6 * (len(bodies) + 1)
+
+
 def test_missing_library_fails_loudly(tmp_path, monkeypatch):
     from paper_1801_00829_amd import _lib as L
     monkeypatch.setattr(L, "_lib", None)
