@@ -172,6 +172,32 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / K * 1e3
 
+    # ---- the same K steps replayed from a HIP graph (one capture of the five calls): what the step costs
+    # without the host launch path; reported beside the eager figure, never as `value`
+    graph = None
+    try:
+        gs = torch.cuda.Stream()
+        gs.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(gs):
+            for name in names:                       # workspace of the capture stream
+                calls[name]()
+        gs.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=gs):
+            for name in names:
+                calls[name]()
+        g.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for k in range(K):
+            g.replay()
+        torch.cuda.synchronize()
+        g_elapsed = time.perf_counter() - tg
+        graph = {"ms_per_step": round(g_elapsed / K * 1e3, 4),
+                 "value": round(gbps(sum(info[n]["bytes"] for n in names), g_elapsed / K), 1), "unit": "GB/s"}
+    except Exception as e:                           # noqa: BLE001 - an extra, must not break the benchmark line
+        graph = {"error": str(e)[:200]}
+
     # ---- floor for the 24 MB Cell workload: a plain read-only kernel (no reduction at all) over a
     # buffer of the same size, cold like the Cell inputs are inside a step (512 MB written in between),
     # in the same event bracket; the Cell operator cannot be faster than this on this device
@@ -232,6 +258,7 @@ def main():
                               "gathers served by L2 (column panels), see traffic") if dominant == "outer" else ""},
         "templates": templates,
         "plan_cache": {"hits": hits, "misses": misses, "compile_ms": round(compile_ms, 1)},
+        "hip_graph_replay": graph,
     }
     if not args.no_cpu_baseline:
         base, refs = _cpu_baseline(names, host)

@@ -100,3 +100,68 @@ def test_calls_on_two_streams_keep_their_own_workspaces():
     for i in range(2):
         for rep in range(12):
             assert abs(float(outs[i][rep].cpu()[0]) - refs[i]) <= 1e-10 * abs(refs[i]), (i, rep)
+
+
+def test_step_of_five_operators_replays_from_a_hip_graph():
+    """After a warm-up on the same stream (plans compiled and loaded, workspace allocated) the calls
+    enqueue kernels only, so a whole step can be captured into a HIP graph and replayed without the
+    host launch path.  Every replay is checked against the oracle on inputs changed (eagerly) since
+    the previous one: arrival counters reset themselves, workspaces are reused, nothing is cached."""
+    import torch
+    import paper_1801_00829_amd as F
+    ws = {n: W.make_workload(n, sc) for n, sc in (("cell", 0.05), ("magg", 0.003), ("row_dense", 0.004),
+                                                  ("row_csr", 0.0004), ("outer", 0.02))}
+    d = {}
+    for n in ("cell", "magg", "row_dense"):
+        d[n] = (to_dev(ws[n]["X"]), dev_sides(ws[n]["sides"]))
+    d["row_csr"] = (dev_csr(*ws["row_csr"]["X"]), dev_sides(ws["row_csr"]["sides"]))
+    d["outer"] = (dev_csr(*ws["outer"]["X"]), to_dev(ws["outer"]["U"]), to_dev(ws["outer"]["V"]))
+    outs = {"cell": torch.empty(1, dtype=torch.float64, device="cuda"),
+            "magg": torch.empty(3, dtype=torch.float64, device="cuda"),
+            "row_dense": torch.empty(ws["row_dense"]["X"].shape[1], dtype=torch.float64, device="cuda"),
+            "row_csr": torch.empty(ws["row_csr"]["X"][3][1], dtype=torch.float64, device="cuda"),
+            "outer": torch.empty(1, dtype=torch.float64, device="cuda")}
+
+    def step():
+        F.fuse_cell(ws["cell"]["expr"], d["cell"][0], d["cell"][1], "full", out=outs["cell"])
+        F.fuse_magg(ws["magg"]["exprs"], d["magg"][0], d["magg"][1], out=outs["magg"])
+        F.fuse_row(ws["row_dense"]["expr"], d["row_dense"][0], d["row_dense"][1], "col_t", out=outs["row_dense"])
+        F.fuse_row(ws["row_csr"]["expr"], d["row_csr"][0], d["row_csr"][1], "col_t", out=outs["row_csr"])
+        F.fuse_outer(ws["outer"]["expr"], d["outer"][0], d["outer"][1], d["outer"][2], [], "full", out=outs["outer"])
+
+    def check(tag):
+        torch.cuda.synchronize()
+        for n in ws:
+            got, ref = outs[n].cpu().numpy(), _oracle(n, ws[n])
+            if n == "magg":
+                for j in range(3):
+                    assert_close(got[j], ref[j], tol=TOL, what="%s %s[%d]" % (tag, n, j))
+            else:
+                assert_close(got, ref, tol=TOL, what="%s %s" % (tag, n))
+
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        step()                                   # warm-up on the capture stream
+    s.synchronize()
+    check("eager")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        step()
+    for rep in range(3):
+        # change the inputs in place (eager work between the replays), on the host copies too
+        f = 1.0 + 0.25 * (rep + 1)
+        for n in ("cell", "magg", "row_dense"):
+            d[n][0].mul_(f)
+            ws[n]["X"] = ws[n]["X"] * f
+        d["row_csr"][0].vals.mul_(f)
+        rp, ci, va, shape = ws["row_csr"]["X"]
+        ws["row_csr"]["X"] = (rp, ci, va * f, shape)
+        d["outer"][1].mul_(f)
+        ws["outer"]["U"] = ws["outer"]["U"] * f
+        for o in outs.values():
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        print("graph replay", rep, flush=True)
+        g.replay()
+        check("replay %d" % rep)
