@@ -25,7 +25,12 @@
  *     with a new descriptor compiles it (hipRTC, host-side, blocking).
  *   - libfuse owns a small per-(device, stream) workspace for block partials;
  *     two calls that overlap on the same stream handle from different host
- *     threads are not supported.
+ *     threads are not supported.  The workspace is allocated (hipMalloc) by the
+ *     first call on a stream and grows to the largest request seen there; a call
+ *     whose plan is cached and loaded and whose workspace is large enough only
+ *     launches kernels (outputs are cleared by a fill kernel, arrival counters
+ *     reset themselves), so after one warm-up call on the capturing stream a
+ *     sequence of calls can be recorded into a HIP graph and replayed.
  *   - Return value: FUSE_OK (0) or a negative fuse_status; on error nothing is
  *     enqueued and `fuse_last_error()` returns a thread-local message
  *     (including the hipRTC log for FUSE_ECOMPILE).
