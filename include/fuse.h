@@ -232,8 +232,13 @@ int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
  *                  cells (i, j) of row i of body * V[j,:]  (the listing's
  *                  vectMultAdd: "scale V_j by w_ij and add it to the output row")
  *   agg LEFT_MM  : out is cols(X) x r, contiguous: out[j,:] = sum over the stored
- *                  cells (i, j) of column j of body * U[i,:]  (the mirrored variant;
- *                  accumulated with fp64 atomics: the order of additions is not fixed)
+ *                  cells (i, j) of column j of body * U[i,:]  (the mirrored variant).
+ *                  The library first transposes the PATTERN of X into its workspace
+ *                  (a counting sort by column, three small kernels on the same stream;
+ *                  about 2 * nnz + 3 * cols(X) offsets) and then walks the columns like
+ *                  RIGHT_MM walks the rows; the cells of a column are added in the order
+ *                  the sort's atomics left them in, which is not fixed from run to run.
+ *                  rows(X) < 2^27 (else a scatter with fp64 atomics on the output).
  * 1 <= r <= 1024.  When V is larger than a few MB, FULL and NONE first build a table of
  * per-row offsets into column panels in the library's workspace (one more kernel on
  * the same stream; (P+1) x rows(X) offsets, P <= 1024 panels) and rely on the

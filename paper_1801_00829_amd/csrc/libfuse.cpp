@@ -1021,9 +1021,13 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
             --UNR;
     }
 
+    // left_mm: by default over the transposed pattern of X (built per call in the workspace) as the right_mm
+    // traversal with U and V exchanged; FUSE_OUTER_LEFT_TRANSPOSE=0 keeps the scatter with fp64 atomics
+    const bool transposed = mode == 3 && env_int("FUSE_OUTER_LEFT_TRANSPOSE", 1) != 0 && X->rows <= 2147483647LL / 16;
+    const int kmode = transposed ? 2 : mode;
     const bool out_vec = vec2 && (!launch || aligned16(out));
     const std::string key = std::string("outer|") + (panels ? "panels|" : "") + prog.key + "|" + side_key(sides, nsides) + "|agg" +
-                            std::to_string(mode) + (mode == 2 && out_vec ? "o" : "") + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
+                            std::to_string(kmode) + (transposed ? "T" : "") + (kmode == 2 && out_vec ? "o" : "") + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
                             std::to_string(EPL) + "u" + std::to_string(UNR) + "b" + std::to_string(BLOCK) + "w" +
                             std::to_string(X->rowptr_is64 != 0);
     std::shared_ptr<Plan> plan;
@@ -1035,7 +1039,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_EPL " + std::to_string(EPL) +
              "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_UNR " + std::to_string(UNR) +
              "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_MODE " +
-             std::to_string(mode) + "\n#define FUSE_OUT_VEC " + std::to_string(out_vec) + "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) +
+             std::to_string(kmode) + "\n#define FUSE_TRANSPOSED " + std::to_string(transposed) + "\n#define FUSE_OUT_VEC " + std::to_string(out_vec) + "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) +
              "\n#define FUSE_NEED_COL " + std::to_string(need_col) + "\n#define FUSE_PANELS " + std::to_string(panels) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_outer_body(prog);
@@ -1054,11 +1058,11 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         return rc;
     if (X->rows == 0 || X->nnz == 0)
         return zero_fill(fn, out, mode == 0 ? 0 : out_count, stream);
-    if (mode == 3 && (rc = zero_fill(fn, out, out_count, stream)))
+    if (mode == 3 && !transposed && (rc = zero_fill(fn, out, out_count, stream)))
         return rc;
     const int cus = rt.num_cus();
     const int NW = BLOCK / 64;
-    int64_t gx = (X->rows + NW - 1) / NW;
+    int64_t gx = ((transposed ? X->cols : X->rows) + NW - 1) / NW;
     gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_OUTER_BLOCKS_PER_CU", 8)));
     size_t pp_doubles = 0;
     if (panels) {
@@ -1071,6 +1075,14 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         pp_doubles = (size_t)(npanels + 1) * (size_t)X->rows * (X->rowptr_is64 ? 8 : 4) / 8 + 1;
     }
     const size_t part_doubles = ((size_t)gx + 15) / 16 * 16;
+    // transposed pattern: column offsets, scratch of the counting sort, row and original index of every cell
+    const size_t rpb = X->rowptr_is64 ? 8 : 4;
+    auto dbl = [](size_t bytes) { return (bytes + 15) / 16 * 2; };           // doubles, 16-byte granules
+    const size_t t_next = dbl((size_t)X->cols * rpb), t_bsum = dbl(transpose_scan_blocks(X->cols) * rpb),
+                 t_ptr = dbl((size_t)(X->cols + 1) * rpb), t_row = dbl((size_t)X->nnz * 4),
+                 t_perm = dbl((size_t)X->nnz * rpb);
+    if (transposed)
+        pp_doubles = t_next + t_bsum + t_ptr + t_row + t_perm;
     Workspace ws;
     if ((rc = rt.workspace(stream, part_doubles + pp_doubles, ws, g_err)))
         return rc;
@@ -1091,6 +1103,24 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     A.partials = ws.partials;
     A.ticket = ws.ticket;
     fill_side_args(A, sides, nsides);
+    if (transposed) {
+        double *base = ws.partials + part_doubles;
+        void *next = base, *bsum = base + t_next, *tptr = base + t_next + t_bsum;
+        int *trow = reinterpret_cast<int *>(base + t_next + t_bsum + t_ptr);
+        void *tperm = base + t_next + t_bsum + t_ptr + t_row;
+        if (transpose_launch(X->rowptr, X->rowptr_is64, X->colidx, X->rows, X->cols, X->nnz, next, bsum, tptr, trow,
+                             tperm, stream))
+            return fail(FUSE_ERUNTIME, "left_mm: launching the pattern transposition failed");
+        A.colidx = trow;
+        A.rowptr = tptr;
+        A.m = X->cols;
+        A.n = X->rows;
+        A.u = V->data;
+        A.v = U->data;
+        A.ldu = V->ld;
+        A.ldv = U->ld;
+        A.panel_ptr = tperm;
+    }
     if (panels) {
         if (!fn.prep)
             return fail(FUSE_ERUNTIME, "panel plan without its preparatory kernel");

@@ -104,4 +104,11 @@ private:
 int check_csr_launch(const void *rowptr, int rowptr_is64, const int *colidx, long long rows, long long cols,
                      long long nnz, unsigned long long *bad, hipStream_t stream);
 
+// Pattern transposition of a CSR matrix (transpose.hip): tptr (n + 1 offsets), trow (row of every cell, by
+// column) and tperm (index of that cell in the original arrays); `next` (n) and `bsum`
+// (transpose_scan_blocks(n)) are scratch.  Offsets have the width of the matrix' own row offsets.  0 on success.
+size_t transpose_scan_blocks(long long n);
+int transpose_launch(const void *rowptr, int rowptr_is64, const int *colidx, long long m, long long n, long long nnz,
+                     void *next, void *bsum, void *tptr, int *trow, void *tperm, hipStream_t stream);
+
 }  // namespace fuse

@@ -540,9 +540,19 @@ def test_outer_rowptr64_and_strided_factors(outer_mapping):
 ALS_W = [("main",), ("neq0",), ("uvdot",), ("mul",)]        # (X != 0) * (U_i . V_j): the ALS-CG update, Sec. 2.2
 
 
-@pytest.mark.parametrize("agg", ["right_mm", "left_mm"])
-def test_outer_mm_on_all_patterns(agg):
+@pytest.fixture(params=["transposed", "atomics"])
+def left_mm_form(request, monkeypatch):
+    """Both forms of left_mm: over the transposed pattern of X (built per call; the default), or a scatter
+    with fp64 atomics."""
+    monkeypatch.setenv("FUSE_OUTER_LEFT_TRANSPOSE", "1" if request.param == "transposed" else "0")
+    return request.param
+
+
+@pytest.mark.parametrize("agg,rowptr64", [("right_mm", False), ("left_mm", False), ("left_mm", True)])
+def test_outer_mm_on_all_patterns(agg, rowptr64, left_mm_form):
     import paper_1801_00829_amd as F
+    if agg == "right_mm" and left_mm_form != "transposed":
+        pytest.skip("the form only concerns left_mm")
     for name, (rp, ci, va), shape in _csr_cases():
         m, n = shape
         for r in (100, 7, 20):
@@ -550,7 +560,9 @@ def test_outer_mm_on_all_patterns(agg):
             rng = np.random.default_rng(31)
             u, v = rng.uniform(size=(m, r)), rng.uniform(size=(n, r))
             x = ops.make_csr(rp, ci, va, shape)
-            got = host(F.fuse_outer(ALS_W, dev_csr(rp, ci, va, shape), to_dev(u), to_dev(v), [], agg))
+            got = host(F.fuse_outer(ALS_W, dev_csr(rp, ci, va, shape, rowptr64), to_dev(u), to_dev(v), [], agg))
+            if agg == "left_mm" and va.size:
+                assert ("#define FUSE_TRANSPOSED 1" in F.last_source()) == (left_mm_form == "transposed")
             ref = unfused.outer(ALS_W, x, u, v, [], agg)
             assert_close(got, ref, scale=max(np.abs(ref).max(), 1e-300) if ref.size else 1.0, what="outer %s %s" % (agg, name))
             # rows / columns without stored cells must be exactly zero
@@ -559,7 +571,7 @@ def test_outer_mm_on_all_patterns(agg):
 
 
 @pytest.mark.parametrize("case", range(8 * MORE))
-def test_outer_mm_random_expressions(case):
+def test_outer_mm_random_expressions(case, left_mm_form):
     import paper_1801_00829_amd as F
     rng = np.random.default_rng(9500 + case)
     m, n, r = [(1, 1, 1), (30, 20, 7), (200, 300, 100), (64, 64, 20)][case % 4]
