@@ -1078,11 +1078,11 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     // transposed pattern: column offsets, scratch of the counting sort, row and original index of every cell
     const size_t rpb = X->rowptr_is64 ? 8 : 4;
     auto dbl = [](size_t bytes) { return (bytes + 15) / 16 * 2; };           // doubles, 16-byte granules
-    const size_t t_next = dbl((size_t)X->cols * rpb), t_bsum = dbl(transpose_scan_blocks(X->cols) * rpb),
+    const size_t t_scratch = transposed ? dbl(transpose_scratch_bytes(X->rows, X->cols, X->nnz, X->rowptr_is64)) : 0,
                  t_ptr = dbl((size_t)(X->cols + 1) * rpb), t_row = dbl((size_t)X->nnz * 4),
                  t_perm = dbl((size_t)X->nnz * rpb);
     if (transposed)
-        pp_doubles = t_next + t_bsum + t_ptr + t_row + t_perm;
+        pp_doubles = t_scratch + t_ptr + t_row + t_perm;
     Workspace ws;
     if ((rc = rt.workspace(stream, part_doubles + pp_doubles, ws, g_err)))
         return rc;
@@ -1105,10 +1105,10 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     fill_side_args(A, sides, nsides);
     if (transposed) {
         double *base = ws.partials + part_doubles;
-        void *next = base, *bsum = base + t_next, *tptr = base + t_next + t_bsum;
-        int *trow = reinterpret_cast<int *>(base + t_next + t_bsum + t_ptr);
-        void *tperm = base + t_next + t_bsum + t_ptr + t_row;
-        if (transpose_launch(X->rowptr, X->rowptr_is64, X->colidx, X->rows, X->cols, X->nnz, next, bsum, tptr, trow,
+        void *scratch = base, *tptr = base + t_scratch;
+        int *trow = reinterpret_cast<int *>(base + t_scratch + t_ptr);
+        void *tperm = base + t_scratch + t_ptr + t_row;
+        if (transpose_launch(X->rowptr, X->rowptr_is64, X->colidx, X->rows, X->cols, X->nnz, scratch, tptr, trow,
                              tperm, stream))
             return fail(FUSE_ERUNTIME, "left_mm: launching the pattern transposition failed");
         A.colidx = trow;

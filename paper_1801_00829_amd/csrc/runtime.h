@@ -105,10 +105,10 @@ int check_csr_launch(const void *rowptr, int rowptr_is64, const int *colidx, lon
                      long long nnz, unsigned long long *bad, hipStream_t stream);
 
 // Pattern transposition of a CSR matrix (transpose.hip): tptr (n + 1 offsets), trow (row of every cell, by
-// column) and tperm (index of that cell in the original arrays); `next` (n) and `bsum`
-// (transpose_scan_blocks(n)) are scratch.  Offsets have the width of the matrix' own row offsets.  0 on success.
-size_t transpose_scan_blocks(long long n);
+// column) and tperm (index of that cell in the original arrays); `scratch` holds transpose_scratch_bytes()
+// bytes, 16-byte aligned.  Offsets have the width of the matrix' own row offsets.  0 on success.
+size_t transpose_scratch_bytes(long long m, long long n, long long nnz, int rowptr_is64);
 int transpose_launch(const void *rowptr, int rowptr_is64, const int *colidx, long long m, long long n, long long nnz,
-                     void *next, void *bsum, void *tptr, int *trow, void *tperm, hipStream_t stream);
+                     void *scratch, void *tptr, int *trow, void *tperm, hipStream_t stream);
 
 }  // namespace fuse
