@@ -15,6 +15,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "runtime.h"
 
@@ -299,7 +300,8 @@ Shape shape_of(long long m, long long n, long long nnz)
     int shift = 0;
     while (((n + (1LL << shift) - 1) >> shift) > MAX_RANGES)
         ++shift;
-    s.two_level = shift <= MAX_RANGE_SHIFT && nnz < 4294967296LL;
+    const char *plain = std::getenv("FUSE_TRANSPOSE_PLAIN");        // (tests: the plain form on small inputs)
+    s.two_level = shift <= MAX_RANGE_SHIFT && nnz < 4294967296LL && !(plain && plain[0] == '1');
     s.shift = shift;
     s.nranges = (int)((n + (1LL << shift) - 1) >> shift);
     // few, large blocks of rows: a block's cells of one range land next to each other (longer runs of writes)

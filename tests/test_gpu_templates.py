@@ -540,11 +540,12 @@ def test_outer_rowptr64_and_strided_factors(outer_mapping):
 ALS_W = [("main",), ("neq0",), ("uvdot",), ("mul",)]        # (X != 0) * (U_i . V_j): the ALS-CG update, Sec. 2.2
 
 
-@pytest.fixture(params=["transposed", "atomics"])
+@pytest.fixture(params=["transposed", "transposed_plain_sort", "atomics"])
 def left_mm_form(request, monkeypatch):
-    """Both forms of left_mm: over the transposed pattern of X (built per call; the default), or a scatter
-    with fp64 atomics."""
-    monkeypatch.setenv("FUSE_OUTER_LEFT_TRANSPOSE", "1" if request.param == "transposed" else "0")
+    """The forms of left_mm: over the transposed pattern of X (built per call by a two-level counting sort,
+    the default; or by the plain one that very wide matrices take), or a scatter with fp64 atomics."""
+    monkeypatch.setenv("FUSE_OUTER_LEFT_TRANSPOSE", "0" if request.param == "atomics" else "1")
+    monkeypatch.setenv("FUSE_TRANSPOSE_PLAIN", "1" if request.param == "transposed_plain_sort" else "0")
     return request.param
 
 
@@ -562,7 +563,7 @@ def test_outer_mm_on_all_patterns(agg, rowptr64, left_mm_form):
             x = ops.make_csr(rp, ci, va, shape)
             got = host(F.fuse_outer(ALS_W, dev_csr(rp, ci, va, shape, rowptr64), to_dev(u), to_dev(v), [], agg))
             if agg == "left_mm" and va.size:
-                assert ("#define FUSE_TRANSPOSED 1" in F.last_source()) == (left_mm_form == "transposed")
+                assert ("#define FUSE_TRANSPOSED 1" in F.last_source()) == left_mm_form.startswith("transposed")
             ref = unfused.outer(ALS_W, x, u, v, [], agg)
             assert_close(got, ref, scale=max(np.abs(ref).max(), 1e-300) if ref.size else 1.0, what="outer %s %s" % (agg, name))
             # rows / columns without stored cells must be exactly zero
