@@ -76,6 +76,21 @@ def test_workload_full_size(name):
         assert_close(_run(w), got, tol=1e-13, what="row_csr rerun")
 
 
+@pytest.mark.parametrize("agg", ["right_mm", "left_mm"])
+def test_outer_product_variants_full_size(agg):
+    """The two product variants of the Outer template at the benchmark shape (1e5 x 1e5, 1e7 stored cells,
+    rank 100) with the weights of the ALS-CG update, (X != 0) * (U t(V)): every output row against the oracle."""
+    import paper_1801_00829_amd as F
+    print("full-size parity: outer", agg, flush=True)
+    w = W.make_workload("outer", 1.0)
+    body = [("main",), ("neq0",), ("uvdot",), ("mul",)]
+    got = host(F.fuse_outer(body, dev_csr(*w["X"]), to_dev(w["U"]), to_dev(w["V"]), [], agg))
+    ref = unfused.outer(body, ops.make_csr(*w["X"]), w["U"], w["V"], [], agg)
+    assert_close(got, ref, tol=TOL, what="outer " + agg)
+    err = np.abs(got.reshape(ref.shape) - ref) / np.maximum(np.abs(ref), 1e-300)     # all terms are positive here
+    assert err.max() <= 1e-12, err.max()
+
+
 def test_calls_on_two_streams_keep_their_own_workspaces():
     """Every (device, stream) pair has its own block partials and arrival counter: operators that
     overlap on two streams (default priorities) must not disturb each other's aggregates."""
