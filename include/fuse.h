@@ -233,9 +233,9 @@ int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
  *                  vectMultAdd: "scale V_j by w_ij and add it to the output row")
  *   agg LEFT_MM  : out is cols(X) x r, contiguous: out[j,:] = sum over the stored
  *                  cells (i, j) of column j of body * U[i,:]  (the mirrored variant).
- *                  The library first transposes the PATTERN of X into its workspace
- *                  (a counting sort by column, a few small kernels on the same stream;
- *                  about 28 bytes per stored cell) and then walks the columns like
+ *                  The library first transposes X into its workspace (a counting sort
+ *                  by column, a few small kernels on the same stream; about 28 bytes
+ *                  per stored cell) and then walks the columns like
  *                  RIGHT_MM walks the rows; the cells of a column are added in the order
  *                  the sort's atomics left them in, which is not fixed from run to run.
  *                  rows(X) < 2^27 (else a scatter with fp64 atomics on the output).

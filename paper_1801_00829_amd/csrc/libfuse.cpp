@@ -1075,14 +1075,14 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         pp_doubles = (size_t)(npanels + 1) * (size_t)X->rows * (X->rowptr_is64 ? 8 : 4) / 8 + 1;
     }
     const size_t part_doubles = ((size_t)gx + 15) / 16 * 16;
-    // transposed pattern: column offsets, scratch of the counting sort, row and original index of every cell
+    // transposed matrix: scratch of the counting sort, column offsets, row and value of every cell
     const size_t rpb = X->rowptr_is64 ? 8 : 4;
     auto dbl = [](size_t bytes) { return (bytes + 15) / 16 * 2; };           // doubles, 16-byte granules
     const size_t t_scratch = transposed ? dbl(transpose_scratch_bytes(X->rows, X->cols, X->nnz, X->rowptr_is64)) : 0,
                  t_ptr = dbl((size_t)(X->cols + 1) * rpb), t_row = dbl((size_t)X->nnz * 4),
-                 t_perm = dbl((size_t)X->nnz * rpb);
+                 t_val = (size_t)X->nnz;
     if (transposed)
-        pp_doubles = t_scratch + t_ptr + t_row + t_perm;
+        pp_doubles = t_scratch + t_ptr + t_row + t_val;
     Workspace ws;
     if ((rc = rt.workspace(stream, part_doubles + pp_doubles, ws, g_err)))
         return rc;
@@ -1107,10 +1107,11 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         double *base = ws.partials + part_doubles;
         void *scratch = base, *tptr = base + t_scratch;
         int *trow = reinterpret_cast<int *>(base + t_scratch + t_ptr);
-        void *tperm = base + t_scratch + t_ptr + t_row;
-        if (transpose_launch(X->rowptr, X->rowptr_is64, X->colidx, X->rows, X->cols, X->nnz, scratch, tptr, trow,
-                             tperm, stream))
+        double *tval = base + t_scratch + t_ptr + t_row;
+        if (transpose_launch(X->rowptr, X->rowptr_is64, X->colidx, X->vals, X->rows, X->cols, X->nnz, scratch, tptr,
+                             trow, tval, stream))
             return fail(FUSE_ERUNTIME, "left_mm: launching the pattern transposition failed");
+        A.x = tval;
         A.colidx = trow;
         A.rowptr = tptr;
         A.m = X->cols;
@@ -1119,7 +1120,6 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         A.v = U->data;
         A.ldu = V->ld;
         A.ldv = U->ld;
-        A.panel_ptr = tperm;
     }
     if (panels) {
         if (!fn.prep)

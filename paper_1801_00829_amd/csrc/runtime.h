@@ -104,11 +104,11 @@ private:
 int check_csr_launch(const void *rowptr, int rowptr_is64, const int *colidx, long long rows, long long cols,
                      long long nnz, unsigned long long *bad, hipStream_t stream);
 
-// Pattern transposition of a CSR matrix (transpose.hip): tptr (n + 1 offsets), trow (row of every cell, by
-// column) and tperm (index of that cell in the original arrays); `scratch` holds transpose_scratch_bytes()
-// bytes, 16-byte aligned.  Offsets have the width of the matrix' own row offsets.  0 on success.
+// Transposition of a CSR matrix (transpose.hip): tptr (n + 1 offsets, of the width of the matrix' own row
+// offsets), trow (row of every cell, by column) and tval (its value); `scratch` holds
+// transpose_scratch_bytes() bytes, 16-byte aligned.  0 on success.
 size_t transpose_scratch_bytes(long long m, long long n, long long nnz, int rowptr_is64);
-int transpose_launch(const void *rowptr, int rowptr_is64, const int *colidx, long long m, long long n, long long nnz,
-                     void *scratch, void *tptr, int *trow, void *tperm, hipStream_t stream);
+int transpose_launch(const void *rowptr, int rowptr_is64, const int *colidx, const double *vals, long long m, long long n,
+                     long long nnz, void *scratch, void *tptr, int *trow, double *tval, hipStream_t stream);
 
 }  // namespace fuse

@@ -1,14 +1,13 @@
-// Pattern transposition of a CSR matrix on the device: for every column the list of (row, cell
-// index) pairs of its stored cells.  Used by the left_mm variant of the Outer template (Table 1),
+// Transposition of a CSR matrix on the device: for every column the list of (row, value) pairs
+// of its stored cells.  Used by the left_mm variant of the Outer template (Table 1),
 // which accumulates into output row j over the stored cells of COLUMN j: with the transposed
 // pattern it becomes the right_mm traversal (one group of lanes owns an output row, no atomics on
 // the output).  A counting sort by column in two levels, so that all counting happens in LDS:
 //   1. the columns are cut into at most 1024 ranges of 2^s columns; blocks of rows count their
 //      cells per range (LDS histogram), an exclusive scan over (range, block) gives every block
-//      its place in every range, and the blocks write (column, row, cell index) there;
+//      its place in every range, and the blocks write (column, row, value) there;
 //   2. one block per range counts its cells per column (LDS), scans the counts -- these are the
-//      column offsets of the transposed pattern -- and moves (row, cell index) to their final
-//      places.
+//      column offsets of the transposed matrix -- and moves (row, value) to their final places.
 // Matrices with more than 1024 * 8192 columns take the plain form instead: one global atomic per
 // cell for the counts and one for the places.  The order of the cells inside a column is
 // whatever the atomics produce.
@@ -45,10 +44,10 @@ __global__ void __launch_bounds__(256) count_kernel(const int *__restrict__ coli
 }
 
 // exclusive prefix sum of the block's thread values; returns this thread's offset, *total = block sum
-template <typename RP>
+template <typename RP, int NT = SCAN_THREADS>
 __device__ __forceinline__ RP block_exclusive_scan(RP v, RP *total)
 {
-    __shared__ RP wsum[SCAN_THREADS / 64];
+    __shared__ RP wsum[NT / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     RP inc = v;
 #pragma unroll
@@ -63,7 +62,7 @@ __device__ __forceinline__ RP block_exclusive_scan(RP v, RP *total)
     __syncthreads();
     RP before = 0, all = 0;
 #pragma unroll
-    for (int w = 0; w < SCAN_THREADS / 64; ++w) {
+    for (int w = 0; w < NT / 64; ++w) {
         if (w < wave)
             before += wsum[w];
         all += wsum[w];
@@ -142,24 +141,26 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_apply_kernel(RP *__restrict
 // ---- two-level form -------------------------------------------------------------------------
 struct __attribute__((aligned(16))) Cell {       // one stored cell between the two levels: one 16-byte store
     int col, row;
-    unsigned long long idx;                      // index in the original arrays
+    double val;
 };
+constexpr int RANGE_THREADS = 1024;       // level 2
+constexpr int PART_THREADS = 1024;        // level 1: 64 rows in flight per block
 constexpr int MAX_RANGES = 1024;
 constexpr int MAX_RANGE_SHIFT = 13;       // 8192 columns per range: 32 KB of LDS counters
 
 // level 1, counting: hist[range * nblk + block] = cells of the block's rows in the column range
 template <typename RP, typename XRP>
-__global__ void __launch_bounds__(256) part_hist_kernel(const XRP *__restrict__ rowptr, const int *__restrict__ colidx,
+__global__ void __launch_bounds__(PART_THREADS) part_hist_kernel(const XRP *__restrict__ rowptr, const int *__restrict__ colidx,
                                                         long long m, long long n, long long nnz, long long rows_per_block,
                                                         int shift, int nranges, RP *__restrict__ hist)
 {
     __shared__ unsigned int cnt[MAX_RANGES];
-    for (int i = threadIdx.x; i < nranges; i += 256)
+    for (int i = threadIdx.x; i < nranges; i += PART_THREADS)
         cnt[i] = 0;
     __syncthreads();
     const int k = threadIdx.x & 15;
     const long long row0 = (long long)blockIdx.x * rows_per_block;
-    for (long long lr = threadIdx.x >> 4; lr < rows_per_block && row0 + lr < m; lr += 16) {
+    for (long long lr = threadIdx.x >> 4; lr < rows_per_block && row0 + lr < m; lr += PART_THREADS / 16) {
         const long long row = row0 + lr;
         long long rs = (long long)rowptr[row], re = (long long)rowptr[row + 1];
         rs = rs < 0 ? 0 : (rs > nnz ? nnz : rs);
@@ -171,24 +172,25 @@ __global__ void __launch_bounds__(256) part_hist_kernel(const XRP *__restrict__ 
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < nranges; i += 256)
+    for (int i = threadIdx.x; i < nranges; i += PART_THREADS)
         hist[(long long)i * gridDim.x + blockIdx.x] = (RP)cnt[i];
 }
 
 // level 1, moving: the same walk; every cell goes to the next free place of its block inside its range
 template <typename RP, typename XRP>
-__global__ void __launch_bounds__(256) part_move_kernel(const XRP *__restrict__ rowptr, const int *__restrict__ colidx,
-                                                        long long m, long long n, long long nnz, long long rows_per_block,
+__global__ void __launch_bounds__(PART_THREADS) part_move_kernel(const XRP *__restrict__ rowptr, const int *__restrict__ colidx,
+                                                        const double *__restrict__ vals, long long m, long long n,
+                                                        long long nnz, long long rows_per_block,
                                                         int shift, int nranges, const RP *__restrict__ place,
                                                         Cell *__restrict__ cells)
 {
     __shared__ RP cursor[MAX_RANGES];
-    for (int i = threadIdx.x; i < nranges; i += 256)
+    for (int i = threadIdx.x; i < nranges; i += PART_THREADS)
         cursor[i] = place[(long long)i * gridDim.x + blockIdx.x];
     __syncthreads();
     const int k = threadIdx.x & 15;
     const long long row0 = (long long)blockIdx.x * rows_per_block;
-    for (long long lr = threadIdx.x >> 4; lr < rows_per_block && row0 + lr < m; lr += 16) {
+    for (long long lr = threadIdx.x >> 4; lr < rows_per_block && row0 + lr < m; lr += PART_THREADS / 16) {
         const long long row = row0 + lr;
         long long rs = (long long)rowptr[row], re = (long long)rowptr[row + 1];
         rs = rs < 0 ? 0 : (rs > nnz ? nnz : rs);
@@ -199,7 +201,7 @@ __global__ void __launch_bounds__(256) part_move_kernel(const XRP *__restrict__ 
                 continue;
             const long long pos = (long long)atomicAdd(&cursor[c >> shift], (RP)1);
             if (pos >= 0 && pos < nnz) {  // (always, unless the arrays change while the call runs)
-                cells[pos] = Cell{(int)c, (int)row, (unsigned long long)e};
+                cells[pos] = Cell{(int)c, (int)row, vals[e]};
             }
         }
     }
@@ -207,10 +209,10 @@ __global__ void __launch_bounds__(256) part_move_kernel(const XRP *__restrict__ 
 
 // level 2: one block per column range
 template <typename RP>
-__global__ void __launch_bounds__(SCAN_THREADS) range_sort_kernel(const Cell *__restrict__ cells, const RP *__restrict__ place,
+__global__ void __launch_bounds__(RANGE_THREADS) range_sort_kernel(const Cell *__restrict__ cells, const RP *__restrict__ place,
                                                                   const RP *__restrict__ total, long long nblk, int shift,
                                                                   long long n, long long nnz, RP *__restrict__ tptr,
-                                                                  int *__restrict__ trow, RP *__restrict__ tperm)
+                                                                  int *__restrict__ trow, double *__restrict__ tval)
 {
     extern __shared__ unsigned int colcnt[];          // 2^shift counters, then cursors
     const int width = 1 << shift;
@@ -220,21 +222,21 @@ __global__ void __launch_bounds__(SCAN_THREADS) range_sort_kernel(const Cell *__
     s0 = s0 < 0 ? 0 : (s0 > nnz ? nnz : s0);
     s1 = s1 < s0 ? s0 : (s1 > nnz ? nnz : s1);
     const long long cbase = b << shift;
-    for (int i = threadIdx.x; i < width; i += SCAN_THREADS)
+    for (int i = threadIdx.x; i < width; i += RANGE_THREADS)
         colcnt[i] = 0;
     __syncthreads();
-    for (long long p = s0 + threadIdx.x; p < s1; p += SCAN_THREADS) {
+    for (long long p = s0 + threadIdx.x; p < s1; p += RANGE_THREADS) {
         const long long cl = (long long)cells[p].col - cbase;
         if (cl >= 0 && cl < width)
             atomicAdd(&colcnt[cl], 1u);
     }
     __syncthreads();
     unsigned int carry = 0;
-    for (int j0 = 0; j0 < width; j0 += SCAN_THREADS) {
+    for (int j0 = 0; j0 < width; j0 += RANGE_THREADS) {
         const int j = j0 + threadIdx.x;
         const unsigned int v = j < width ? colcnt[j] : 0u;
         unsigned int tot;
-        const unsigned int off = block_exclusive_scan(v, &tot) + carry;
+        const unsigned int off = block_exclusive_scan<unsigned int, RANGE_THREADS>(v, &tot) + carry;
         if (j < width) {
             colcnt[j] = off;
             if (cbase + j < n)
@@ -245,7 +247,7 @@ __global__ void __launch_bounds__(SCAN_THREADS) range_sort_kernel(const Cell *__
     if (b == gridDim.x - 1 && threadIdx.x == 0)
         tptr[n] = (RP)s1;
     __syncthreads();
-    for (long long p = s0 + threadIdx.x; p < s1; p += SCAN_THREADS) {
+    for (long long p = s0 + threadIdx.x; p < s1; p += RANGE_THREADS) {
         const Cell c = cells[p];
         const long long cl = (long long)c.col - cbase;
         if (cl < 0 || cl >= width)
@@ -253,7 +255,7 @@ __global__ void __launch_bounds__(SCAN_THREADS) range_sort_kernel(const Cell *__
         const long long pos = s0 + (long long)atomicAdd(&colcnt[cl], 1u);
         if (pos < s1) {
             trow[pos] = c.row;
-            tperm[pos] = (RP)c.idx;
+            tval[pos] = c.val;
         }
     }
 }
@@ -261,8 +263,9 @@ __global__ void __launch_bounds__(SCAN_THREADS) range_sort_kernel(const Cell *__
 // scatter: cell e of row i in column c goes to slot next[c]++ of column c.  16 lanes per row.
 template <typename RP, typename XRP>
 __global__ void __launch_bounds__(256) scatter_kernel(const XRP *__restrict__ rowptr, const int *__restrict__ colidx,
-                                                      long long m, long long n, long long nnz, RP *__restrict__ next,
-                                                      int *__restrict__ trow, RP *__restrict__ tperm)
+                                                      const double *__restrict__ vals, long long m, long long n,
+                                                      long long nnz, RP *__restrict__ next, int *__restrict__ trow,
+                                                      double *__restrict__ tval)
 {
     const int k = threadIdx.x & 15;
     const long long row = ((long long)blockIdx.x * 256 + threadIdx.x) >> 4;
@@ -278,7 +281,7 @@ __global__ void __launch_bounds__(256) scatter_kernel(const XRP *__restrict__ ro
         const long long pos = (long long)atomicAdd(&next[c], (RP)1);
         if (pos >= 0 && pos < nnz) {      // (always, unless the arrays change while the call runs)
             trow[pos] = (int)row;
-            tperm[pos] = (RP)e;
+            tval[pos] = vals[e];
         }
     }
 }
@@ -315,10 +318,10 @@ Shape shape_of(long long m, long long n, long long nnz)
 size_t align16(size_t b) { return (b + 15) / 16 * 16; }
 
 template <typename RP, typename XRP>
-int transpose_typed(const void *rowptr, const int *colidx, long long m, long long n, long long nnz, char *scratch,
-                    void *tptr_, int *trow, void *tperm_, hipStream_t stream)
+int transpose_typed(const void *rowptr, const int *colidx, const double *vals, long long m, long long n, long long nnz,
+                    char *scratch, void *tptr_, int *trow, double *tval, hipStream_t stream)
 {
-    RP *tptr = (RP *)tptr_, *tperm = (RP *)tperm_;
+    RP *tptr = (RP *)tptr_;
     const Shape sh = shape_of(m, n, nnz);
     if (!sh.two_level) {
         RP *next = (RP *)scratch, *bsum = (RP *)(scratch + align16((size_t)n * sizeof(RP)));
@@ -329,7 +332,7 @@ int transpose_typed(const void *rowptr, const int *colidx, long long m, long lon
         scan_bsums_kernel<RP><<<1, SCAN_THREADS, 0, stream>>>(bsum, nb);
         scan_apply_kernel<RP><<<(unsigned)nb, SCAN_THREADS, 0, stream>>>(next, n, bsum, tptr, (RP *)nullptr);
         const long long gs = (m * 16 + 255) / 256;
-        scatter_kernel<RP, XRP><<<(unsigned)gs, 256, 0, stream>>>((const XRP *)rowptr, colidx, m, n, nnz, next, trow, tperm);
+        scatter_kernel<RP, XRP><<<(unsigned)gs, 256, 0, stream>>>((const XRP *)rowptr, colidx, vals, m, n, nnz, next, trow, tval);
         return hipGetLastError() == hipSuccess ? 0 : -1;
     }
     // scratch: hist | block sums of its scan | grand total | the cells by range
@@ -339,15 +342,15 @@ int transpose_typed(const void *rowptr, const int *colidx, long long m, long lon
     RP *bsum = (RP *)q;              q += align16((size_t)nb * sizeof(RP));
     RP *total = (RP *)q;             q += 16;
     Cell *cells = (Cell *)q;
-    part_hist_kernel<RP, XRP><<<(unsigned)sh.nblk, 256, 0, stream>>>((const XRP *)rowptr, colidx, m, n, nnz, sh.rows_per_block,
+    part_hist_kernel<RP, XRP><<<(unsigned)sh.nblk, PART_THREADS, 0, stream>>>((const XRP *)rowptr, colidx, m, n, nnz, sh.rows_per_block,
                                                                     sh.shift, sh.nranges, hist);
     scan_sums_kernel<RP><<<(unsigned)nb, SCAN_THREADS, 0, stream>>>(hist, sh.nhist, bsum);
     scan_bsums_kernel<RP><<<1, SCAN_THREADS, 0, stream>>>(bsum, nb);
     scan_apply_kernel<RP><<<(unsigned)nb, SCAN_THREADS, 0, stream>>>(hist, sh.nhist, bsum, (RP *)nullptr, total);
-    part_move_kernel<RP, XRP><<<(unsigned)sh.nblk, 256, 0, stream>>>((const XRP *)rowptr, colidx, m, n, nnz, sh.rows_per_block,
-                                                                    sh.shift, sh.nranges, hist, cells);
-    range_sort_kernel<RP><<<(unsigned)sh.nranges, SCAN_THREADS, (size_t)4 << sh.shift, stream>>>(
-        cells, hist, total, sh.nblk, sh.shift, n, nnz, tptr, trow, tperm);
+    part_move_kernel<RP, XRP><<<(unsigned)sh.nblk, PART_THREADS, 0, stream>>>((const XRP *)rowptr, colidx, vals, m, n, nnz,
+                                                                    sh.rows_per_block, sh.shift, sh.nranges, hist, cells);
+    range_sort_kernel<RP><<<(unsigned)sh.nranges, RANGE_THREADS, (size_t)4 << sh.shift, stream>>>(
+        cells, hist, total, sh.nblk, sh.shift, n, nnz, tptr, trow, tval);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -365,14 +368,15 @@ size_t transpose_scratch_bytes(long long m, long long n, long long nnz, int rowp
     return align16((size_t)sh.nhist * rpb) + align16((size_t)nb * rpb) + 16 + (size_t)nnz * sizeof(Cell);
 }
 
-int transpose_launch(const void *rowptr, int rowptr_is64, const int *colidx, long long m, long long n, long long nnz,
-                     void *scratch, void *tptr, int *trow, void *tperm, hipStream_t stream)
+int transpose_launch(const void *rowptr, int rowptr_is64, const int *colidx, const double *vals, long long m, long long n,
+                     long long nnz, void *scratch, void *tptr, int *trow, double *tval, hipStream_t stream)
 {
     if (m <= 0 || n <= 0 || m > 2147483647LL / 16)
         return -1;
     if (rowptr_is64)
-        return transpose_typed<unsigned long long, long long>(rowptr, colidx, m, n, nnz, (char *)scratch, tptr, trow, tperm, stream);
-    return transpose_typed<unsigned int, int>(rowptr, colidx, m, n, nnz, (char *)scratch, tptr, trow, tperm, stream);
+        return transpose_typed<unsigned long long, long long>(rowptr, colidx, vals, m, n, nnz, (char *)scratch, tptr, trow, tval,
+                                                              stream);
+    return transpose_typed<unsigned int, int>(rowptr, colidx, vals, m, n, nnz, (char *)scratch, tptr, trow, tval, stream);
 }
 
 }  // namespace fuse
