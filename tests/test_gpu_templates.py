@@ -549,11 +549,8 @@ def left_mm_form(request, monkeypatch):
     return request.param
 
 
-@pytest.mark.parametrize("agg,rowptr64", [("right_mm", False), ("left_mm", False), ("left_mm", True)])
-def test_outer_mm_on_all_patterns(agg, rowptr64, left_mm_form):
+def _outer_mm_on_all_patterns(agg, rowptr64, left_mm_form):
     import paper_1801_00829_amd as F
-    if agg == "right_mm" and left_mm_form != "transposed":
-        pytest.skip("the form only concerns left_mm")
     for name, (rp, ci, va), shape in _csr_cases():
         m, n = shape
         for r in (100, 7, 20):
@@ -569,6 +566,15 @@ def test_outer_mm_on_all_patterns(agg, rowptr64, left_mm_form):
             # rows / columns without stored cells must be exactly zero
             empty = (np.diff(rp) == 0) if agg == "right_mm" else (np.bincount(ci, minlength=n) == 0)
             assert not got.reshape(-1, r)[empty].any()
+
+
+def test_outer_right_mm_on_all_patterns():
+    _outer_mm_on_all_patterns("right_mm", False, "")
+
+
+@pytest.mark.parametrize("rowptr64", [False, True])
+def test_outer_left_mm_on_all_patterns(rowptr64, left_mm_form):
+    _outer_mm_on_all_patterns("left_mm", rowptr64, left_mm_form)
 
 
 @pytest.mark.parametrize("case", range(8 * MORE))
