@@ -703,17 +703,17 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     if (G <= 0 || C <= 0) {
         const double avg = m > 0 ? (double)X->nnz / (double)m : 1.0;
         const int cover = next_pow2((int64_t)(avg + 1.5 * std::sqrt(avg) + 0.999));
-        C = cover >= 16 ? 4 : (cover >= 4 ? 2 : 1);
+        C = cover >= 4 ? 4 : cover;            // (4 cells = one 16-byte load of column indices; 2 per lane: 1.6x slower)
         G = std::min(64, std::max(1, cover / C));
         if (cover > 256)
             C = 4, G = 64;
     }
     const int RS = std::max(1, env_int("FUSE_CSR_RS", 1));
     const int BLOCK = std::max(64, env_int("FUSE_CSR_BLOCK", 1024));
-    // Very short rows (a lane group per row would cover <= 8 cells, i.e. a mean of up to 5 cells per
-    // row): the streaming skeleton, where a wave reads runs of whole rows as contiguous cells.
-    // Measured on 1000 columns with 1e8 stored cells, t(X)(Xv): 3 cells per row 285 us against 500 us
-    // for lane groups, 10 per row 264 against 234, 100 per row 344 against 267.
+    // Very short rows (a mean of up to 5.5 cells): the streaming skeleton, where a wave reads runs of
+    // whole rows as contiguous cells.  Measured on 1000 columns, t(X)(Xv), 1e8 stored cells: 3 per row
+    // 285 us against 500 us for lane groups, 10 per row 264 against 234; 5e7 stored cells: 4 per row
+    // 135 against 157, 5 per row 132 against 144, 6 per row 126 against 119, 8 per row 124 against 115.
     // FUSE_CSR_STREAM: 0 never, 1 always, 2 by this rule.
     const int stream_mode = env_int("FUSE_CSR_STREAM", 2);
     const int SC = 4;                                    // cells per lane of the streaming skeleton (8: slower, 442 us on config 4)
@@ -723,7 +723,8 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     for (int k = 0; k < nsides; ++k)
         need_rid |= prog.side_used[k] && (sides[k].kind == FUSE_SIDE_MATRIX || sides[k].kind == FUSE_SIDE_COLVEC);
     // (bodies with k-vectors run in the lane-group form only)
-    const bool streaming = kd == 0 && (stream_mode == 1 || (stream_mode == 2 && (G * C <= 8 || !need_rid)));
+    const double mean_len = m > 0 ? (double)X->nnz / (double)m : 0.0;
+    const bool streaming = kd == 0 && (stream_mode == 1 || (stream_mode == 2 && (mean_len <= 5.5 || !need_rid)));
 
     // LDS plan: the column accumulator first, then staged row-vector sides if they fit
     int nrv = 0;
