@@ -92,3 +92,44 @@ def test_sparse_cell_and_outer_beyond_2_31_cells(big):
         finally:
             os.environ.pop("FUSE_OUTER_PANELS", None)
         assert got == expect, (panels, got, expect)
+
+
+def test_dense_beyond_2_31_elements():
+    """Dense inputs with more than 2^31 elements: flat Cell / MAgg index arithmetic, the 2-D form and the
+    dense Row skeleton; integer-valued inputs, so every expected value is exact."""
+    import torch
+    import paper_1801_00829_amd as F
+    free, _ = torch.cuda.mem_get_info()
+    if free < 60 * 2**30:
+        pytest.skip("needs 60 GiB of free device memory")
+    m, n = 2_200_000, 1000
+    assert m * n > 2**31
+    x = torch.ones(m, n, dtype=torch.float64, device="cuda")
+    x[-1, -1] = 3.0                                   # the very last element must be seen exactly once
+    x[2**31 // n, (2**31) % n] = 5.0                  # and the one at flat index 2^31
+    y = torch.full((m, n), 2.0, dtype=torch.float64, device="cuda")
+    total = float(m) * n + 2.0 + 4.0
+    assert F.fuse_cell([("main",), ("side", 0), ("mul",)], x, [("matrix", y)], "full").cpu().numpy()[0] == 2.0 * total
+    got = F.fuse_magg([[("main",), ("side", 0), ("mul",)], [("main",), ("pow2",)]], x, [("matrix", y)]).cpu().numpy()
+    assert got[0] == 2.0 * total and got[1] == float(m) * n - 2.0 + 9.0 + 25.0
+    # 2-D form: row vector side; column and row aggregates
+    rv = (torch.arange(n, dtype=torch.float64, device="cuda") % 4) + 1
+    cols = F.fuse_cell([("main",), ("side", 0), ("mul",)], x, [("rowvec", rv)], "col").cpu()
+    expect = rv.cpu() * m
+    expect[-1] += 2.0 * rv[-1].item()
+    expect[(2**31) % n] += 4.0 * rv[(2**31) % n].item()
+    assert torch.equal(cols, expect)
+    rows = F.fuse_cell([("main",)], x, [], "row")
+    assert rows[0].item() == n and rows[-1].item() == n + 2.0 and rows[2**31 // n].item() == n + 4.0
+    # dense Row: t(X) %*% (X %*% v) with v = 1
+    v = torch.ones(n, dtype=torch.float64, device="cuda")
+    out = F.fuse_row([("main",), ("side", 0), ("dot",), ("main",), ("mul",)], x, [("rowvec", v)], "col_t").cpu().numpy()
+    # q_i = n except the two marked rows; out[c] = sum_i x_ic q_i
+    q_last, q_mid = n + 2.0, n + 4.0
+    base = float(m - 2) * n + q_last + q_mid
+    exp = np.full(n, base)
+    exp[-1] += 2.0 * q_last
+    exp[(2**31) % n] += 4.0 * q_mid
+    assert np.array_equal(out, exp)
+    del x, y
+    torch.cuda.empty_cache()
