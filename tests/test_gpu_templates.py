@@ -520,6 +520,25 @@ def test_outer_closed_forms_patterns_and_index_exactness(outer_mapping):
     assert_close(got, plans.outer_sum_x_log_uv(x, u, np.ones((50, 100))), what="outer zero rows")
 
 
+@pytest.mark.parametrize("r", [1, 2, 513, 1000, 1024])
+def test_outer_extreme_ranks(r, outer_mapping):
+    """The smallest and the largest ranks the Outer template takes (1 <= r <= 1024), all variants."""
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(1300 + r)
+    m, n = 70, 90
+    rp, ci, va = W.csr_bernoulli(m, n, 0.1, 1300 + r)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    u, v = rng.uniform(size=(m, r)), rng.uniform(size=(n, r))
+    body = [("main",), ("uvdot",), ("const", 1e-15), ("add",), ("log",), ("mul",)]
+    xd, ud, vd = dev_csr(rp, ci, va, (m, n)), to_dev(u), to_dev(v)
+    for agg in ("full", "none", "right_mm", "left_mm"):
+        got = host(F.fuse_outer(body, xd, ud, vd, [], agg))
+        ref = unfused.outer(body, x, u, v, [], agg)
+        assert_close(got, ref, tol=1e-10, what="outer rank %d %s" % (r, agg))
+    with pytest.raises(F.FuseError):
+        F.fuse_outer(body, xd, to_dev(rng.uniform(size=(m, 1025))), to_dev(rng.uniform(size=(n, 1025))), [], "full")
+
+
 def test_outer_rowptr64_and_strided_factors(outer_mapping):
     import paper_1801_00829_amd as F
     from oracle import plans
