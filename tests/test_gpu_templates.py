@@ -152,6 +152,42 @@ def test_magg_random_and_equals_separate_cells(case):
         assert_close(got[j], one[0], scale=scale, tol=1e-13, what="magg vs cell [%d]" % j)
 
 
+@pytest.mark.parametrize("form", ["flat", "2d", "csr"])
+def test_magg_sixteen_aggregates_and_eight_sides(form):
+    """The largest multi-aggregate: 16 bodies over 8 side inputs (all matrices: flat form; mixed with
+    vectors and scalars: 2-D form; over a sparse main input)."""
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(6500)
+    m, n = 333, 257
+    x = rng.uniform(-1.5, 1.5, size=(m, n))
+    if form == "flat":
+        sides = [("matrix", rng.uniform(-1.5, 1.5, size=(m, n))) for _ in range(8)]
+    else:
+        sides = [("matrix", rng.uniform(-1.5, 1.5, size=(m, n))), ("colvec", rng.uniform(-1.5, 1.5, size=m)),
+                 ("rowvec", rng.uniform(-1.5, 1.5, size=n)), ("scalar", np.array(0.3)),
+                 ("matrix", rng.uniform(-1.5, 1.5, size=(m, n))), ("colvec", rng.uniform(-1.5, 1.5, size=m)),
+                 ("rowvec", rng.uniform(-1.5, 1.5, size=n)), ("scalar", np.array(-1.1))]
+    # body j: X * side_(j % 8) * side_((j + 3) % 8) + X * j   (sparse-safe)
+    exprs = [[("main",), ("side", j % 8), ("mul",), ("side", (j + 3) % 8), ("mul",), ("main",), ("const", float(j)), ("mul",),
+              ("add",)] for j in range(16)]
+    sd = dev_sides(sides)
+    if form == "csr":
+        rp, ci, va = W.csr_bernoulli(m, n, 0.15, 6501)
+        xs = ops.make_csr(rp, ci, va, (m, n))
+        got = host(F.fuse_magg_csr(exprs, dev_csr(rp, ci, va, (m, n)), sd))
+        ref = unfused.magg_csr(exprs, xs, sides)
+        scales = [np.abs(unfused.cell_csr(e, xs, sides, "none")).sum() for e in exprs]
+    else:
+        got = host(F.fuse_magg(exprs, to_dev(x), sd))
+        ref = unfused.magg(exprs, x, sides)
+        scales = [np.abs(unfused.cell(e, x, sides, "none")).sum() for e in exprs]
+    assert got.shape == (16,)
+    for j in range(16):
+        assert_close(got[j], ref[j], scale=max(scales[j], 1e-300), what="magg16 %s [%d]" % (form, j))
+    with pytest.raises(F.FuseError):
+        F.fuse_magg(exprs + [exprs[0]], to_dev(x), sd)            # 17 aggregates
+
+
 @pytest.mark.parametrize("case", range(6 * MORE))
 def test_magg_with_vector_sides_and_strided_inputs(case):
     """MAgg bodies that need the 2-D form of the skeleton: row / column vector sides, views with a
