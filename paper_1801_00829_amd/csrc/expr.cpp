@@ -272,15 +272,33 @@ std::string program_key(const Program &prog)
 
 namespace {
 
-// Emits node `id` as a C expression.  `vec_side`/`scal_side`: names of the
-// arrays that hold vector-kind and scalar-kind side values; cross-lane
-// reductions that are already available are read from red[]; `d` is the Outer
-// inner product.  For k-vector nodes `j` selects the component.
+// Emits the value of node `id` as C statements, one named constant per operator node (a body may
+// be thousands of operators deep; nested as ONE expression it would exceed the compiler's bracket
+// depth), and returns the operand text that stands for it.  `vec_side` / `scal_side`: names of the
+// arrays that hold vector-kind and scalar-kind side values; cross-lane reductions that are already
+// available are read from red[]; `d` is the Outer inner product.  For k-vector nodes `j` selects the
+// component.  Statements collect in `stmts` (take() hands them over); names stay valid until reset().
 struct Emitter {
     const Program &p;
     const char *vec_side;
     const char *scal_side;
-    std::string gen(int id, int j = 0) const
+    std::string indent = "    ";
+    std::string stmts;
+    std::map<std::pair<int, int>, std::string> done;
+
+    void reset(const std::string &ind = "    ")
+    {
+        stmts.clear();
+        done.clear();
+        indent = ind;
+    }
+    std::string take()
+    {
+        std::string t;
+        t.swap(stmts);
+        return t;
+    }
+    std::string ref(int id, int j = 0)
     {
         const Node &n = p.nodes[id];
         switch (n.op) {
@@ -296,48 +314,58 @@ struct Emitter {
         case FUSE_OP_DOT:
             if (n.red >= 0)
                 return "red[" + std::to_string(n.red) + "]";
-            {   // over the k entries of k-vectors: written out
-                std::string sum = "(";
-                for (int c = 0; c < p.kdim; ++c) {
-                    if (c)
-                        sum += " + ";
-                    sum += n.op == FUSE_OP_DOT ? "(" + gen(n.a, c) + " * " + gen(n.b, c) + ")" : gen(n.a, c);
-                }
-                return sum + ")";
-            }
+            break;
         default: break;
         }
-        if (n.b < 0) {
-            const std::string x = gen(n.a, j);
+        const int jj = n.kind == KIND_K ? j : 0;
+        const auto key = std::make_pair(id, jj);
+        auto it = done.find(key);
+        if (it != done.end())
+            return it->second;
+        std::string e;
+        if (n.op == FUSE_OP_ROWSUM || n.op == FUSE_OP_DOT) {      // over the k entries of k-vectors: written out
+            for (int c = 0; c < p.kdim; ++c) {
+                if (c)
+                    e += " + ";
+                e += n.op == FUSE_OP_DOT ? "(" + ref(n.a, c) + " * " + ref(n.b, c) + ")" : ref(n.a, c);
+            }
+        } else if (n.b < 0) {
+            const std::string x = ref(n.a, j);
             switch (n.op) {
-            case FUSE_OP_NEG: return "(-" + x + ")";
-            case FUSE_OP_ABS: return "fabs(" + x + ")";
-            case FUSE_OP_SQRT: return "sqrt(" + x + ")";
-            case FUSE_OP_EXP: return "exp(" + x + ")";
-            case FUSE_OP_LOG: return "log(" + x + ")";
-            case FUSE_OP_POW2: return "fuse_pow2(" + x + ")";
-            case FUSE_OP_SIGN: return "fuse_sign(" + x + ")";
-            case FUSE_OP_NEQ0: return "fuse_neq0(" + x + ")";
-            case FUSE_OP_SIGMOID: return "fuse_sigmoid(" + x + ")";
+            case FUSE_OP_NEG: e = "-" + x; break;
+            case FUSE_OP_ABS: e = "fabs(" + x + ")"; break;
+            case FUSE_OP_SQRT: e = "sqrt(" + x + ")"; break;
+            case FUSE_OP_EXP: e = "exp(" + x + ")"; break;
+            case FUSE_OP_LOG: e = "log(" + x + ")"; break;
+            case FUSE_OP_POW2: e = "fuse_pow2(" + x + ")"; break;
+            case FUSE_OP_SIGN: e = "fuse_sign(" + x + ")"; break;
+            case FUSE_OP_NEQ0: e = "fuse_neq0(" + x + ")"; break;
+            case FUSE_OP_SIGMOID: e = "fuse_sigmoid(" + x + ")"; break;
+            default: e = "0.0"; break;
+            }
+        } else {
+            const std::string x = ref(n.a, j), y = ref(n.b, j);
+            switch (n.op) {
+            case FUSE_OP_ADD: e = x + " + " + y; break;
+            case FUSE_OP_SUB: e = x + " - " + y; break;
+            case FUSE_OP_MUL: e = x + " * " + y; break;
+            case FUSE_OP_DIV: e = x + " / " + y; break;
+            case FUSE_OP_MIN: e = "fuse_min(" + x + ", " + y + ")"; break;
+            case FUSE_OP_MAX: e = "fuse_max(" + x + ", " + y + ")"; break;
+            case FUSE_OP_POW: e = "pow(" + x + ", " + y + ")"; break;
+            case FUSE_OP_LT: e = "fuse_cmp(" + x + " < " + y + ")"; break;
+            case FUSE_OP_LE: e = "fuse_cmp(" + x + " <= " + y + ")"; break;
+            case FUSE_OP_GT: e = "fuse_cmp(" + x + " > " + y + ")"; break;
+            case FUSE_OP_GE: e = "fuse_cmp(" + x + " >= " + y + ")"; break;
+            case FUSE_OP_EQ: e = "fuse_cmp(" + x + " == " + y + ")"; break;
+            case FUSE_OP_NE: e = "fuse_cmp(" + x + " != " + y + ")"; break;
+            default: e = "0.0"; break;
             }
         }
-        const std::string x = gen(n.a, j), y = gen(n.b, j);
-        switch (n.op) {
-        case FUSE_OP_ADD: return "(" + x + " + " + y + ")";
-        case FUSE_OP_SUB: return "(" + x + " - " + y + ")";
-        case FUSE_OP_MUL: return "(" + x + " * " + y + ")";
-        case FUSE_OP_DIV: return "(" + x + " / " + y + ")";
-        case FUSE_OP_MIN: return "fuse_min(" + x + ", " + y + ")";
-        case FUSE_OP_MAX: return "fuse_max(" + x + ", " + y + ")";
-        case FUSE_OP_POW: return "pow(" + x + ", " + y + ")";
-        case FUSE_OP_LT: return "fuse_cmp(" + x + " < " + y + ")";
-        case FUSE_OP_LE: return "fuse_cmp(" + x + " <= " + y + ")";
-        case FUSE_OP_GT: return "fuse_cmp(" + x + " > " + y + ")";
-        case FUSE_OP_GE: return "fuse_cmp(" + x + " >= " + y + ")";
-        case FUSE_OP_EQ: return "fuse_cmp(" + x + " == " + y + ")";
-        case FUSE_OP_NE: return "fuse_cmp(" + x + " != " + y + ")";
-        }
-        return "0.0";
+        const std::string name = "v" + std::to_string(id) + "_" + std::to_string(jj);
+        stmts += indent + "const double " + name + " = " + e + ";\n";
+        done[key] = name;
+        return name;
     }
 };
 
@@ -347,8 +375,10 @@ std::string emit_cell_body(const Program &prog)
 {
     Emitter em{prog, "s", "s"};
     std::string src = "__device__ __forceinline__ void fuse_body(double a, const double *s, double *r)\n{\n";
-    for (size_t j = 0; j < prog.roots.size(); ++j)
-        src += "    r[" + std::to_string(j) + "] = " + em.gen(prog.roots[j]) + ";\n";
+    for (size_t j = 0; j < prog.roots.size(); ++j) {
+        const std::string v = em.ref(prog.roots[j]);
+        src += em.take() + "    r[" + std::to_string(j) + "] = " + v + ";\n";
+    }
     src += "}\n";
     return src;
 }
@@ -356,8 +386,9 @@ std::string emit_cell_body(const Program &prog)
 std::string emit_outer_body(const Program &prog)
 {
     Emitter em{prog, "s", "s"};
-    return "__device__ __forceinline__ double fuse_body(double a, double d, const double *s)\n{\n"
-           "    return " + em.gen(prog.roots[0]) + ";\n}\n";
+    const std::string v = em.ref(prog.roots[0]);
+    return "__device__ __forceinline__ double fuse_body(double a, double d, const double *s)\n{\n" + em.take() +
+           "    return " + v + ";\n}\n";
 }
 
 // Row bodies.  Arguments of the generated functions:
@@ -389,19 +420,21 @@ std::string emit_row_body(const Program &prog)
            "                                           double *part)\n{\n";
     for (int s = 0; s < prog.nstage; ++s) {
         src += "    if (st == " + std::to_string(s) + ") {\n";
+        em.reset("        ");
         for (int id : prog.reductions) {
             const Node &n = prog.nodes[id];
             if (n.level != s + 1)
                 continue;
             if (n.op == FUSE_OP_MATMULT) {
-                src += "        { const double t_ = " + em.gen(n.a) + ";\n";
+                const std::string t = em.ref(n.a);
+                src += em.take();
                 for (int j = 0; j < prog.kdim; ++j)
-                    src += "          part[" + std::to_string(n.red + j) + "] += t_ * kb[" +
+                    src += "        part[" + std::to_string(n.red + j) + "] += " + t + " * kb[" +
                            std::to_string(n.arg * FUSE_MAX_K + j) + "];\n";
-                src += "        }\n";
             } else {
-                std::string term = n.op == FUSE_OP_DOT ? "(" + em.gen(n.a) + " * " + em.gen(n.b) + ")" : em.gen(n.a);
-                src += "        part[" + std::to_string(n.red) + "] += " + term + ";\n";
+                const std::string x = em.ref(n.a);
+                const std::string term = n.op == FUSE_OP_DOT ? x + " * " + em.ref(n.b) : x;
+                src += em.take() + "        part[" + std::to_string(n.red) + "] += " + term + ";\n";
             }
         }
         src += "    }\n";
@@ -411,36 +444,53 @@ std::string emit_row_body(const Program &prog)
     // row-vector results (k of them for a multi-aggregate), or row (x) k-vector: k values per element
     src += "__device__ __forceinline__ void fuse_final_elems(double a, const double *sv, const double *rsc,\n"
            "                                                 const double *kv, const double *red, double *r)\n{\n";
+    em.reset();
     if (prog.result_kind == KIND_VK) {
         const Node &n = prog.nodes[root];
-        src += "    const double t_ = " + em.gen(n.a) + ";\n";
-        for (int j = 0; j < kd; ++j)
-            src += "    r[" + std::to_string(j) + "] = t_ * " + em.gen(n.b, j) + ";\n";
+        const std::string t = em.ref(n.a);
+        src += em.take();
+        for (int j = 0; j < kd; ++j) {
+            const std::string w = em.ref(n.b, j);
+            src += em.take() + "    r[" + std::to_string(j) + "] = " + t + " * " + w + ";\n";
+        }
     } else {
-        for (int j = 0; j < kres; ++j)
-            src += "    r[" + std::to_string(j) + "] = " +
-                   (prog.result_kind == KIND_V ? em.gen(prog.roots[j]) : std::string("0.0")) + ";\n";
+        for (int j = 0; j < kres; ++j) {
+            const std::string v = prog.result_kind == KIND_V ? em.ref(prog.roots[j]) : std::string("0.0");
+            src += em.take() + "    r[" + std::to_string(j) + "] = " + v + ";\n";
+        }
     }
     src += "}\n";
     // the k-vector factor of a row (x) k-vector result on its own (the matrix-unit skeleton forms the
     // outer products itself)
     src += "__device__ __forceinline__ void fuse_outer_kvec(const double *rsc, const double *kv, const double *red,\n"
            "                                                double *r)\n{\n";
-    for (int j = 0; j < kd; ++j)
-        src += "    r[" + std::to_string(j) + "] = " +
-               (prog.result_kind == KIND_VK ? em.gen(prog.nodes[root].b, j) : std::string("0.0")) + ";\n";
+    em.reset();
+    for (int j = 0; j < kd; ++j) {
+        const std::string v = prog.result_kind == KIND_VK ? em.ref(prog.nodes[root].b, j) : std::string("0.0");
+        src += em.take() + "    r[" + std::to_string(j) + "] = " + v + ";\n";
+    }
     src += "}\n";
     src += "__device__ __forceinline__ double fuse_final_elem(double a, const double *sv, const double *rsc,\n"
-           "                                                  const double *kv, const double *red)\n{\n    return " +
-           (prog.result_kind == KIND_V ? em.gen(root) : std::string("0.0")) + ";\n}\n";
+           "                                                  const double *kv, const double *red)\n{\n";
+    em.reset();
+    {
+        const std::string v = prog.result_kind == KIND_V ? em.ref(root) : std::string("0.0");
+        src += em.take() + "    return " + v + ";\n}\n";
+    }
     src += "__device__ __forceinline__ double fuse_final_scalar(const double *rsc, const double *kv,\n"
-           "                                                    const double *red)\n{\n    return " +
-           (prog.result_kind == KIND_S ? em.gen(root) : std::string("0.0")) + ";\n}\n";
+           "                                                    const double *red)\n{\n";
+    em.reset();
+    {
+        const std::string v = prog.result_kind == KIND_S ? em.ref(root) : std::string("0.0");
+        src += em.take() + "    return " + v + ";\n}\n";
+    }
     src += "__device__ __forceinline__ void fuse_final_kvec(const double *rsc, const double *kv, const double *red,\n"
            "                                                double *r)\n{\n";
-    for (int j = 0; j < kd; ++j)
-        src += "    r[" + std::to_string(j) + "] = " +
-               (prog.result_kind == KIND_K ? em.gen(root, j) : std::string("0.0")) + ";\n";
+    em.reset();
+    for (int j = 0; j < kd; ++j) {
+        const std::string v = prog.result_kind == KIND_K ? em.ref(root, j) : std::string("0.0");
+        src += em.take() + "    r[" + std::to_string(j) + "] = " + v + ";\n";
+    }
     src += "}\n";
     return src;
 }

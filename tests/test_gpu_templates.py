@@ -688,7 +688,7 @@ def test_als_cg_update_as_two_fused_operators():
     np.testing.assert_allclose(got, ((d != 0) * (u @ v.T)) @ v + 1e-6 * u * rr[:, None], rtol=1e-11)
 
 
-@pytest.mark.parametrize("nops", [1, 8, 40])
+@pytest.mark.parametrize("nops", [1, 8, 40, 300])
 def test_row_long_chain_expression(nops):
     """sum(f(X / rowSums(X))) with f a chain of `nops` scalar multiplications (the expression of
     the instruction-footprint experiment, Sec. 5.2): one reduction stage, then a long body."""

@@ -59,20 +59,23 @@ def test_prepare_compiles_the_five_workloads_and_caches(F):
     F.prepare_cell(XYZ, (1000, 1000), two, "full")
     assert F.last_kernel().startswith("fuse_cell_")
     src = F.last_source()
-    assert "r[0] = ((a * s[0]) * s[1]);" in src and "fuse_grid_finish" in src
+    assert re.search(r"const double (v\d+_0) = a \* s\[0\];\s+const double (v\d+_0) = \1 \* s\[1\];\s+r\[0\] = \2;", src)
+    assert "fuse_grid_finish" in src
     F.prepare_magg([XYZ[:3], [("main",), ("side", 1), ("mul",)], [("main",), ("pow2",)]], (100000, 1000), two)
-    assert "r[2] = fuse_pow2(a);" in F.last_source()
+    assert re.search(r"const double (v\d+_0) = fuse_pow2\(a\);\s+r\[2\] = \1;", F.last_source())
     F.prepare_row([("main",), ("side", 0), ("dot",), ("side", 1), ("mul",), ("main",), ("mul",)], (1000000, 100),
                   [("rowvec", None), ("colvec", None)], "col_t")
     src = F.last_source()
-    assert "part[0] += (a * sv[0]);" in src and "return ((red[0] * rsc[1]) * a);" in src
+    assert "part[0] += a * sv[0];" in src
+    assert re.search(r"const double (v\d+_0) = red\[0\] \* rsc\[1\];\s+const double (v\d+_0) = \1 \* a;\s+return \2;", src)
     assert "#define FUSE_G 16" in src and "#define FUSE_EPL 4" in src and "#define FUSE_VEC 2" in src
     F.prepare_row([("main",), ("side", 0), ("dot",), ("main",), ("mul",)], (10000000, 1000), [("rowvec", None)],
                   "col_t", nnz=100000000)
     assert F.last_kernel().startswith("fuse_row_csr_") and "#define FUSE_C " in F.last_source()
     F.prepare_outer([("main",), ("uvdot",), ("const", 1e-15), ("add",), ("log",), ("mul",)], (100000, 100000), 100,
                     10000000)
-    assert "return (a * log((d + (0x1.203af9ee75616p-50))));" in F.last_source()
+    assert re.search(r"const double (v\d+_0) = d \+ \(0x1\.203af9ee75616p-50\);\s+const double (v\d+_0) = log\(\1\);\s+"
+                     r"const double (v\d+_0) = a \* \2;\s+return \3;", F.last_source())
     hits, misses, ms = F.cache_stats()
     assert (hits, misses) == (0, 5) and ms > 0
     # equal descriptors are compiled once (plan cache)
@@ -86,7 +89,7 @@ def test_prepare_compiles_the_five_workloads_and_caches(F):
 def test_constants_round_trip_exactly(F):
     for c in (1e-15, 0.1, -2.5e300, 5e-324):
         F.prepare_cell([("main",), ("const", c), ("add",)], (4, 4), [], "full")
-        lit = re.search(r"r\[0\] = \(a \+ \((-?0x[0-9a-fp.+-]+)\)\);", F.last_source()).group(1)
+        lit = re.search(r"= a \+ \((-?0x[0-9a-fp.+-]+)\);", F.last_source()).group(1)
         assert float.fromhex(lit) == c
 
 
@@ -173,7 +176,7 @@ def test_row_type_checking_and_sparse_safety(F):
     nested = [("main",), ("main",), ("rowsum",), ("mul",), ("rowsum",)]
     F.prepare_row(nested, (100, 10), [], "none")
     src = F.last_source()
-    assert "#define FUSE_NSTAGE 2" in src and "part[1] += (a * red[0]);" in src
+    assert "#define FUSE_NSTAGE 2" in src and re.search(r"const double (v\d+_0) = a \* red\[0\];\s+part\[1\] \+= \1;", src)
     # CSR: sparse-safe bodies compile, others are rejected with FUSE_EDESC
     F.prepare_row([("main",), ("side", 0), ("mul",), ("abs",)], (100, 10), [("matrix", None)], "col", nnz=50)
     for bad in ([("main",), ("const", 1.0), ("add",)], [("main",), ("exp",)],
@@ -250,6 +253,23 @@ def test_every_operator_compiles(F):
     F.prepare_cell(expr, (16, 16), [("colvec", None)], "row")              # 2-D form of the Cell skeleton
     assert F.last_kernel().startswith("fuse_cell2d_")
     F.prepare_outer(expr + [("uvdot",), ("mul",)], (16, 16), 5, 20, [("rowvec", None)], "none")
+
+
+def test_descriptor_length_limits(F):
+    """A body may have up to 4096 tokens: the longest one parses and compiles (hipRTC, no device), one
+    token more is rejected; so is an empty body."""
+    body = [("main",)]
+    for i in range(2047):
+        body += [("const", 1.0 + 1.0 / (i + 2)), ("mul",)]
+    assert len(body) == 4095
+    body += [("abs",)]
+    assert len(body) == 4096
+    F.prepare_cell(body, (16, 16), [], "full")
+    with pytest.raises(F.FuseError) as e:
+        F.prepare_cell(body + [("neg",)], (16, 16), [], "full")
+    assert e.value.code == -1
+    with pytest.raises(F.FuseError):
+        F.prepare_cell([], (16, 16), [], "full")
 
 
 def test_plan_cache_is_thread_safe(F):
