@@ -724,7 +724,11 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
         need_rid |= prog.side_used[k] && (sides[k].kind == FUSE_SIDE_MATRIX || sides[k].kind == FUSE_SIDE_COLVEC);
     // (bodies with k-vectors run in the lane-group form only)
     const double mean_len = m > 0 ? (double)X->nnz / (double)m : 0.0;
-    const bool streaming = kd == 0 && (stream_mode == 1 || (stream_mode == 2 && (mean_len <= 5.5 || !need_rid)));
+    // LDS the streaming form needs per block beside column sums and staged row vectors: a histogram of
+    // 64 * SC + 4 counters and 65 row totals per row aggregate, per wave
+    const int64_t stream_fixed = (int64_t)(BLOCK / 64) * ((64 * SC + 4) * 4 + (int64_t)std::max(prog.nred, 1) * 65 * 8) + 2048;
+    const bool streaming = kd == 0 && stream_fixed <= 120 * 1024 &&
+                           (stream_mode == 1 || (stream_mode == 2 && (mean_len <= 5.5 || !need_rid)));
 
     // LDS plan: the column accumulator first, then staged row-vector sides if they fit
     int nrv = 0;
@@ -732,7 +736,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
         nrv += prog.side_used[k] && sides[k].kind == FUSE_SIDE_ROWVEC;
     // one block per CU: most of the 160 KB of LDS can go to the column sums and the staged row vectors
     // (the streaming form keeps per-wave histograms and row totals there as well)
-    const int64_t lds_budget = streaming ? 96 * 1024 : 144 * 1024;
+    const int64_t lds_budget = streaming ? std::min<int64_t>(96 * 1024, 156 * 1024 - stream_fixed) : 144 * 1024;
     // column sums: a per-block LDS vector while it fits, else fp64 atomics on the output
     const bool col_acc = ac == 3 && rk != KIND_K;          // per-column running sums (k per column for OUTERK)
     const bool cols_global = col_acc && n * nacck * 8 > lds_budget - 4096;
@@ -787,6 +791,8 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
         out_count = n * kd;
     if (m == 0)
         return zero_fill(fn, out, out_count, stream);
+    if (out_count == 0)                        // e.g. column sums of a matrix without columns: nothing to write
+        return 0;
 
     const int cus = rt.num_cus();
     const int NW = BLOCK / 64;

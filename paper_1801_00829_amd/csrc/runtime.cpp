@@ -185,6 +185,8 @@ int Runtime::resident_blocks_per_cu(hipFunction_t f, int block)
 int Runtime::launch(hipFunction_t f, unsigned gx, unsigned gy, unsigned block, hipStream_t stream,
                     const void *args, size_t arg_bytes, std::string &err)
 {
+    if (gx == 0 || gy == 0 || block == 0)       // nothing to do; an empty grid is not a valid launch
+        return 0;
     void *config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, const_cast<void *>(args),
                       HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_bytes, HIP_LAUNCH_PARAM_END};
     hipError_t e = hipModuleLaunchKernel(f, gx, gy, 1, block, 1, 1, 0, stream, nullptr, config);

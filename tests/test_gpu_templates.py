@@ -868,3 +868,69 @@ def test_row_matrix_rhs_strided_sides_and_limits(rhs_form):
     with pytest.raises(F.FuseError) as e:       # shapes: the right-hand side must have cols(X) rows
         F.fuse_row(TXXV, to_dev(x), [("rhs", to_dev(np.ones((n + 1, k))))], "col_t")
     assert e.value.code == -2
+
+
+# ------------------------------------------------------------ more edge cases ---
+
+def test_zero_sized_inputs_everywhere():
+    """Matrices without rows, without columns or without stored cells through every entry point: zero
+    sums, empty outputs, no launch on empty grids."""
+    import torch
+    import paper_1801_00829_amd as F
+    z = lambda *shape: torch.zeros(shape, dtype=torch.float64, device="cuda")
+    dot = [("main",), ("side", 0), ("dot",), ("main",), ("mul",)]
+    for m, n in ((0, 7), (5, 0), (0, 0)):
+        x = z(m, n)
+        assert host(F.fuse_cell([("main",)], x, [], "full")).tolist() == [0.0]
+        assert host(F.fuse_cell([("main",)], x, [], "row")).tolist() == [0.0] * m
+        assert host(F.fuse_cell([("main",)], x, [], "col")).tolist() == [0.0] * n
+        assert host(F.fuse_cell([("main",)], x, [], "none")).size == 0
+        assert host(F.fuse_magg([[("main",)], [("main",), ("pow2",)]], x, [])).tolist() == [0.0, 0.0]
+        assert host(F.fuse_row(dot, x, [("rowvec", z(n))], "col_t")).tolist() == [0.0] * n
+        assert host(F.fuse_row([("main",), ("rowsum",)], x, [], "none")).tolist() == [0.0] * m
+        # the same shapes as CSR without stored cells
+        xs = F.Csr(torch.zeros(m + 1, dtype=torch.int32, device="cuda"), torch.zeros(0, dtype=torch.int32, device="cuda"),
+                   z(0), (m, n))
+        F.check_csr(xs)
+        for form in ("0", "1"):
+            import os
+            os.environ["FUSE_CSR_STREAM"] = form
+            try:
+                assert host(F.fuse_row(dot, xs, [("rowvec", z(n))], "col_t")).tolist() == [0.0] * n
+                assert host(F.fuse_row([("main",)], xs, [], "row")).tolist() == [0.0] * m
+                assert host(F.fuse_row([("main",)], xs, [], "full")).tolist() == [0.0]
+                assert host(F.fuse_row([("main",)], xs, [], "none")).size == 0
+                assert host(F.fuse_cell_csr([("main",), ("pow2",)], xs, [], "full")).tolist() == [0.0]
+                assert host(F.fuse_magg_csr([[("main",)], [("main",), ("abs",)]], xs, [])).tolist() == [0.0, 0.0]
+            finally:
+                os.environ.pop("FUSE_CSR_STREAM", None)
+        r = 3
+        for agg, count in (("full", 1), ("none", 0), ("right_mm", m * r), ("left_mm", n * r)):
+            got = host(F.fuse_outer([("main",), ("uvdot",), ("mul",)], xs, z(m, r), z(n, r), [], agg))
+            assert got.size == count and not got.any(), (m, n, agg)
+
+
+def test_row_body_with_the_most_reductions_and_stages():
+    """64 row aggregates in one stage (the most a body may have; 65 are rejected), and five nested stages."""
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(71)
+    m, n = 150, 130
+    x = rng.uniform(0.5, 1.5, size=(m, n))
+    body = [("main",), ("const", 1.0), ("mul",), ("rowsum",)]
+    for i in range(2, 65):
+        body += [("main",), ("const", float(i)), ("mul",), ("rowsum",), ("add",)]
+    got = host(F.fuse_row(body, to_dev(x), [], "none"))
+    assert_close(got, unfused.row_dense(body, x, [], "none"), what="64 reductions")
+    rp, ci, va = W.csr_bernoulli(m, n, 0.1, 72)
+    got = host(F.fuse_row(body, dev_csr(rp, ci, va, (m, n)), [], "none"))
+    assert_close(got, unfused.row_csr(body, ops.make_csr(rp, ci, va, (m, n)), [], "none"), what="64 reductions, CSR")
+    with pytest.raises(F.FuseError):
+        F.fuse_row(body + [("main",), ("const", 65.0), ("mul",), ("rowsum",), ("add",)], to_dev(x), [], "none")
+    # five stages: s1 = rowsum(X); s2 = rowsum(X / s1); s3 = rowsum(X * s2) ...
+    nested = [("main",), ("rowsum",)]
+    for i in range(4):
+        nested = [("main",)] + nested + [("div",) if i % 2 == 0 else ("mul",), ("rowsum",)]
+    for agg in ("none", "full"):
+        got = host(F.fuse_row(nested, to_dev(x), [], agg))
+        assert_close(got, unfused.row_dense(nested, x, [], agg), tol=1e-9, what="five stages " + agg)
+    assert "#define FUSE_NSTAGE 5" in F.last_source()
