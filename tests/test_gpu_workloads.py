@@ -180,3 +180,23 @@ def test_step_of_five_operators_replays_from_a_hip_graph():
         print("graph replay", rep, flush=True)
         g.replay()
         check("replay %d" % rep)
+
+
+def test_cache_clear_between_calls():
+    """fuse_cache_clear drops the compiled plans and frees the workspaces (after the caller has synchronised);
+    the next calls compile and allocate again and give the same results."""
+    import torch
+    import paper_1801_00829_amd as F
+    w = W.make_workload("row_csr", 0.0005)
+    x, s = dev_csr(*w["X"]), dev_sides(w["sides"])
+    wc = W.make_workload("cell", 0.05)
+    xc, sc = to_dev(wc["X"]), dev_sides(wc["sides"])
+    first = (host(F.fuse_row(w["expr"], x, s, "col_t")), host(F.fuse_cell(wc["expr"], xc, sc, "full")))
+    for _ in range(2):
+        torch.cuda.synchronize()
+        F.cache_clear()
+        assert F.cache_stats()[:2] == (0, 0)
+        again = (host(F.fuse_row(w["expr"], x, s, "col_t")), host(F.fuse_cell(wc["expr"], xc, sc, "full")))
+        assert F.cache_stats()[1] == 2                      # both plans were compiled anew
+        assert_close(again[0], first[0], tol=1e-13, what="row_csr after clear")
+        assert np.array_equal(again[1], first[1])
