@@ -64,6 +64,13 @@ def _expr(tokens):
     return res
 
 
+def _on_gpu(t, what):
+    """Kernels dereference the pointer on the device: a host tensor would fault the GPU, not raise."""
+    if not t.is_cuda:
+        raise ValueError("%s must be a CUDA (HIP) tensor, got device %s" % (what, t.device))
+    return t
+
+
 def _dense(t, rows=None, cols=None):
     """2-D (or 1-D) float64 tensor with unit column stride -> Dense descriptor."""
     import torch
@@ -74,6 +81,7 @@ def _dense(t, rows=None, cols=None):
         return L.Dense(None, r, c, int(t[2]) if len(t) > 2 else max(c, 1))
     if t.dtype != torch.float64:
         raise TypeError("libfuse matrices are float64")
+    _on_gpu(t, "matrix")
     if t.dim() == 1:
         t = t.view(-1, 1) if cols == 1 else t.view(1, -1)
     if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
@@ -86,6 +94,7 @@ def _dense(t, rows=None, cols=None):
 
 def _sides(sides, m, n):
     """[(kind, tensor | float | shape-tuple)] -> (Side array, count)."""
+    import torch
     arr = (L.Side * max(len(sides), 1))()
     for k, (kind, val) in enumerate(sides):
         arr[k].kind = SIDE[kind]
@@ -101,12 +110,18 @@ def _sides(sides, m, n):
                 arr[k].m = L.Dense(None, m, 1, 1)
             else:
                 v = val.view(-1, 1) if val.dim() == 1 else val
+                if v.dtype != torch.float64:
+                    raise TypeError("libfuse vectors are float64")
+                _on_gpu(v, "column-vector side")
                 arr[k].m = L.Dense(v.data_ptr(), v.shape[0], 1, max(int(v.stride(0)), 1))
         elif kind == "rowvec":
             if isinstance(val, tuple) or val is None:
                 arr[k].m = L.Dense(None, 1, n, max(n, 1))
             else:
                 v = val.reshape(1, -1) if val.dim() == 1 else val
+                if v.dtype != torch.float64:
+                    raise TypeError("libfuse vectors are float64")
+                _on_gpu(v, "row-vector side")
                 if v.shape[0] != 1 and v.shape[1] == 1:      # an n x 1 column used by column index
                     if v.stride(0) != 1:
                         raise ValueError("row-vector side must be contiguous")
@@ -127,6 +142,8 @@ def _csr(x):
         return L.CsrDesc(None, None, None, int(rowptr), m, n, int(vals))
     if colidx.dtype != torch.int32 or vals.dtype != torch.float64:
         raise TypeError("CSR needs int32 column indices and float64 values")
+    for t_, what in ((rowptr, "CSR row offsets"), (colidx, "CSR column indices"), (vals, "CSR values")):
+        _on_gpu(t_, what)
     if rowptr.dtype not in (torch.int32, torch.int64):
         raise TypeError("CSR row offsets must be int32 or int64")
     if not (rowptr.is_contiguous() and colidx.is_contiguous() and vals.is_contiguous()):
@@ -148,8 +165,8 @@ def _out(out, count, like):
     import torch
     if out is None:
         out = torch.empty(int(count), dtype=torch.float64, device=like.device)
-    elif out.dtype != torch.float64 or not out.is_contiguous() or out.numel() < count:
-        raise ValueError("out must be a contiguous float64 tensor with at least %d elements" % count)
+    elif out.dtype != torch.float64 or not out.is_contiguous() or out.numel() < count or not out.is_cuda:
+        raise ValueError("out must be a contiguous float64 CUDA tensor with at least %d elements" % count)
     return out
 
 

@@ -255,6 +255,23 @@ def test_every_operator_compiles(F):
     F.prepare_outer(expr + [("uvdot",), ("mul",)], (16, 16), 5, 20, [("rowvec", None)], "none")
 
 
+def test_binding_rejects_host_tensors(F):
+    """A host tensor's pointer would be dereferenced on the device (a GPU fault, not an error): the binding
+    refuses it before calling the library."""
+    import torch
+    x = torch.ones(4, 4, dtype=torch.float64)
+    empty_csr = F.Csr(torch.zeros(5, dtype=torch.int32), torch.zeros(0, dtype=torch.int32),
+                      torch.zeros(0, dtype=torch.float64), (4, 4))
+    for call in (lambda: F.fuse_cell([("main",)], x, [], "full"),
+                 lambda: F.fuse_magg([[("main",)]], x, []),
+                 lambda: F.fuse_row([("main",), ("rowsum",)], x, [], "none"),
+                 lambda: F.fuse_row([("main",)], empty_csr, [], "full"),
+                 lambda: F.fuse_outer([("uvdot",)], empty_csr, x, x, [], "full"),
+                 lambda: F.check_csr(empty_csr)):
+        with pytest.raises(ValueError, match="CUDA"):
+            call()
+
+
 def test_descriptor_length_limits(F):
     """A body may have up to 4096 tokens: the longest one parses and compiles (hipRTC, no device), one
     token more is rejected; so is an empty body."""
