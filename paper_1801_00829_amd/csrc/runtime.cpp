@@ -187,6 +187,11 @@ int Runtime::launch(hipFunction_t f, unsigned gx, unsigned gy, unsigned block, h
 {
     if (gx == 0 || gy == 0 || block == 0)       // nothing to do; an empty grid is not a valid launch
         return 0;
+    if (gx > 2147483647u || gy > 65535u || block > 1024u) {
+        err = "internal: launch shape out of range (" + std::to_string(gx) + " x " + std::to_string(gy) + " blocks of " +
+              std::to_string(block) + " threads)";
+        return FUSE_ERUNTIME;
+    }
     void *config[] = {HIP_LAUNCH_PARAM_BUFFER_POINTER, const_cast<void *>(args),
                       HIP_LAUNCH_PARAM_BUFFER_SIZE, &arg_bytes, HIP_LAUNCH_PARAM_END};
     hipError_t e = hipModuleLaunchKernel(f, gx, gy, 1, block, 1, 1, 0, stream, nullptr, config);
