@@ -479,10 +479,23 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
     if (WPR > 1)          // (more rows in flight per block were tried: no gain at k = 4, spills at k = 10)
         RS = 1;
 
+    // contiguous rows that are narrow (at most 8 lanes per row; with 8-byte vectors, an odd row length, at
+    // most 32: beyond that the direct loads of a row are long enough and 5.8 against 6.7 TB/s were measured
+    // at 301 columns): the wave's rows are fetched as one contiguous span with 16-byte loads and handed out through LDS
+    // (FUSE_ROW_LDSX=0 switches it off); the span is a whole number of 16-byte vectors, at most 8 KB
+    bool ldsx = WPR == 1 && stripes == 1 && (G <= 8 || (VEC == 1 && G <= 32)) && n >= 1 && X->ld == n && (!launch || aligned16(X->data)) &&
+                env_int("FUSE_ROW_LDSX", 1) != 0;
+    if (ldsx && VEC == 1 && env_int("FUSE_ROW_RS", 0) <= 0)
+        RS = EPL <= 4 ? 4 : (EPL <= 8 ? 2 : 1);        // 8-byte vectors: more rows per pass, the same registers
+    {
+        const int64_t span = (int64_t)(64 / G) * RS * n;
+        if (span % 2 != 0 || span > 1024)
+            ldsx = false;
+    }
     const std::string key = std::string("rowdense|") + pkey + "|rk" + std::to_string(rk) + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(ac) + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
                             std::to_string(EPL) + "r" + std::to_string(RS) + "w" + std::to_string(WPR) + "nt" +
-                            std::to_string(env_int("FUSE_NT", 1));
+                            std::to_string(env_int("FUSE_NT", 1)) + (ldsx ? "x" + std::to_string(n) : "");
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, name_prefix, [&](const std::string &name) {
         std::string s = kSrcArgs;
@@ -492,7 +505,8 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_EPL " + std::to_string(EPL) +
              "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_RS " + std::to_string(RS) +
              "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_AGG " + std::to_string(ac) +
-             "\n#define FUSE_WPR " + std::to_string(WPR) + "\n";
+             "\n#define FUSE_WPR " + std::to_string(WPR) + "\n#define FUSE_LDSX " + std::to_string(ldsx) +
+             "\n#define FUSE_NCOLS " + std::to_string(n) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_row_body(prog);
         s += kSrcRowDense;

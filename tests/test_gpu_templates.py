@@ -307,6 +307,54 @@ def test_row_dense_closed_forms_and_odd_layouts():
     assert_close(got, plans.row_tx_w_xv(x, v, w), what="row strided")
 
 
+NARROW_SHAPES = [(600011, 2), (300007, 8), (150001, 29), (100003, 30), (70001, 50), (66003, 63), (40001, 101),
+                 (1, 8), (5, 29), (129, 7), (64, 1), (4097, 3)]
+
+
+@pytest.mark.parametrize("form", ["staged", "direct"])
+@pytest.mark.parametrize("shape", NARROW_SHAPES)
+def test_row_dense_narrow_rows(shape, form, monkeypatch):
+    """Narrow contiguous rows and odd row lengths: the waves fetch the contiguous span of their rows with
+    16-byte loads and hand it out through shared memory (the row counts span several passes of every wave
+    and a ragged last span); FUSE_ROW_LDSX=0 keeps the direct loads covered.  Matrix and column-vector
+    sides keep their direct loads and must still line up with the rows."""
+    import paper_1801_00829_amd as F
+    monkeypatch.setenv("FUSE_ROW_LDSX", "1" if form == "staged" else "0")
+    F.cache_clear()              # last_source() is the text of the last compilation: compile here
+    m, n = shape
+    rng = np.random.default_rng(7300 + 13 * n + m % 97)
+    x = rng.uniform(-1.5, 1.5, size=(m, n))
+    sides = _sides(rng, m, n)
+    xd, sd = to_dev(x), dev_sides(sides)
+    expr = [("main",), ("side", 2), ("dot",), ("side", 1), ("mul",), ("main",), ("mul",), ("side", 0), ("add",)]
+    none_ref = unfused.row_dense(expr, x, sides, "none")
+    for agg in ("none", "row", "col_t", "full"):
+        print("row narrow", shape, form, agg, flush=True)
+        got = host(F.fuse_row(expr, xd, sd, agg))
+        ref = unfused.row_dense(expr, x, sides, agg)
+        assert_close(got.reshape(ref.shape), ref, scale=_abs_scale(none_ref, agg.replace("col_t", "col"), m, n),
+                     tol=1e-9, what="row narrow %s" % agg)
+        assert ("#define FUSE_LDSX 1" in F.last_source()) == (form == "staged")
+    # per-row scalar results
+    expr_s = [("main",), ("side", 2), ("dot",), ("side", 1), ("add",)]
+    got = host(F.fuse_row(expr_s, xd, sd, "none"))
+    assert_close(got.reshape(-1), unfused.row_dense(expr_s, x, sides, "none").reshape(-1), tol=1e-9, what="row narrow scalar")
+
+
+def test_row_dense_narrow_rows_with_a_row_stride_are_loaded_directly():
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(7400)
+    m, n = 5000, 8
+    xb = rng.normal(size=(m, n + 4))
+    v = rng.normal(size=n)
+    expr = [("main",), ("side", 0), ("dot",), ("main",), ("mul",)]
+    F.cache_clear()
+    got = host(F.fuse_row(expr, to_dev(xb)[:, 2:2 + n], [("rowvec", to_dev(v))], "col_t"))
+    assert "#define FUSE_LDSX 0" in F.last_source()
+    assert_close(got, unfused.row_dense(expr, xb[:, 2:2 + n], [("rowvec", v)], "col_t").reshape(-1),
+                 scale=np.abs((xb[:, 2:2 + n] @ v)[:, None] * xb[:, 2:2 + n]).sum(0).max(), what="row narrow strided")
+
+
 def test_row_dense_empty_and_limits():
     import torch
     import paper_1801_00829_amd as F
