@@ -37,6 +37,9 @@ const char *kSrcRowDense =
 const char *kSrcRowMfma =
 #include "skel_row_mfma.inc"
     ;
+const char *kSrcRowMfmaWave =
+#include "skel_row_mfma_wave.inc"
+    ;
 const char *kSrcRowCsr =
 #include "skel_row_csr.inc"
     ;
@@ -314,6 +317,12 @@ bool mfma_pattern(const Program &prog, const fuse_side *sides, int nsides, int &
     return true;
 }
 
+// one wave per 16-row tile: at most 7 column tiles, contiguous rows
+bool mfma_wave_form(const fuse_dense *X, bool launch)
+{
+    return X->cols <= 112 && X->ld == X->cols && (!launch || aligned16(X->data)) && env_int("FUSE_MFMA_WAVE_FORM", 1) != 0;
+}
+
 int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense *X, const fuse_side *sides,
                   int nsides, int vside, double *out, hipStream_t stream, bool launch)
 {
@@ -325,6 +334,69 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
     const int64_t nct = (n + 15) / 16;                       // 16-column tiles
     const int64_t np = nct * 16 + 1;                         // odd LDS row pitch
     const int64_t nvec = (n + VEC - 1) / VEC;
+    // few columns and contiguous rows: every wave works alone on its own tiles (FUSE_MFMA_WAVE_FORM=0: never).
+    // Measured on 3.2 GB, t(X)(XV) / logistic regression core, k = 8, against the block form below: n = 16
+    // 1.3 / 1.7 against 3.7 / 5.4 ms, n = 32 0.94 / 1.36 against 2.1 / 2.9, n = 64 0.83 / 1.13 against 1.26 / 1.56,
+    // n = 100 0.86 / 1.10 against 1.15 / 1.23; with 8 column tiles (n = 128) the registers no longer hold the
+    // travelling tile, V and the running sums (0.93 / 1.18 - 1.45 against 0.95 / 1.0 - 1.1): the block form stays.
+    if (mfma_wave_form(X, launch)) {
+        const int64_t lds = (16 * np + 16 * 17) * 8;
+        // waves per SIMD the registers are budgeted for: two (256 registers each), or one when the body holds
+        // per-row k-vector sides of 8 and more classes next to V, the running sums and the travelling tile
+        // (1e7 x 100, multinomial logistic regression core: k = 8 2.2 against 2.4 ms, k = 16 2.5 against 5.9 ms)
+        bool kvec_side = false;
+        for (int q = 0; q < nsides; ++q)
+            kvec_side = kvec_side || (prog.side_used[q] && sides[q].kind == FUSE_SIDE_KVEC);
+        int wpe = env_int("FUSE_MFMA_WPE", 0);
+        if (wpe != 1 && wpe != 2)
+            wpe = (kvec_side && kd >= 8) ? 1 : 2;
+        const std::string key = std::string("rowmfmaw|") + pkey + "|" + side_key(sides, nsides) + "|n" + std::to_string(n) +
+                                "nt" + std::to_string(env_int("FUSE_NT", 1)) + "e" + std::to_string(wpe);
+        std::shared_ptr<Plan> plan;
+        int rc = rt.plan(key, "fuse_row_mfma_wave", [&](const std::string &name) {
+            std::string s = kSrcArgs;
+            s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 1)) + "\n";
+            s += kSrcCommon;
+            s += "#define FUSE_KERNEL_NAME " + name + "\n";
+            s += "#define FUSE_NCOLS " + std::to_string(n) + "\n#define FUSE_NP " + std::to_string(np) + "\n#define FUSE_NCT " +
+                 std::to_string(nct) + "\n#define FUSE_VSIDE " + std::to_string(vside) + "\n#define FUSE_WPE " + std::to_string(wpe) + "\n";
+            s += side_tables(sides, nsides, prog.side_used);
+            s += emit_row_body(prog);
+            s += kSrcRowMfmaWave;
+            g_last_source = s;
+            return s;
+        }, plan, g_err);
+        if (rc)
+            return rc;
+        g_last_kernel = plan->kernel_name;
+        if (!launch)
+            return 0;
+        Plan::Loaded fn;
+        if ((rc = rt.load(*plan, fn, g_err)))
+            return rc;
+        if (m == 0 || n == 0)
+            return zero_fill(fn, out, n * kd, stream);
+        const int64_t ntiles = (m + 15) / 16;
+        // one-wave blocks: as many per CU as their LDS tiles allow, at most 8 (two per SIMD: their registers)
+        const int64_t wpc = std::max<int64_t>(1, std::min<int64_t>((158 * 1024) / lds, env_int("FUSE_MFMA_WAVES_PER_CU", 4 * wpe)));
+        const int64_t gx = std::max<int64_t>(1, std::min<int64_t>(ntiles, (int64_t)rt.num_cus() * wpc));
+        Workspace ws;
+        if ((rc = rt.workspace(stream, (size_t)gx * (size_t)(n * kd), ws, g_err)))
+            return rc;
+        fuse_kargs A;
+        std::memset(&A, 0, sizeof A);
+        A.x = X->data;
+        A.m = m;
+        A.n = n;
+        A.ld = X->ld;
+        A.out = out;
+        A.partials = ws.partials;
+        A.ticket = ws.ticket;
+        fill_side_args(A, sides, nsides);
+        if ((rc = rt.launch(fn.main, (unsigned)gx, 1, 64, stream, &A, sizeof A, g_err)))
+            return rc;
+        return run_combine(fn, ws.partials, (int)gx, (int)(n * kd), out, stream);
+    }
     // waves per block (FUSE_MFMA_WAVES, default 8), fewer if the LDS next to the tile does not hold that many
     // partial products (16 x 17 doubles each)
     int NWAVE = env_int("FUSE_MFMA_WAVES", 8);
@@ -413,7 +485,11 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         int vside = -1;
         // (measured against the vector form: equal at k = 4 for n = 784, 2.6x faster at k = 8 for n = 256,
         //  3.2x at k = 10 for n = 784; slower for k = 4 at n = 100 and n = 1000)
-        const int min_k = env_int("FUSE_MFMA_MIN_K", 5);
+        //  with one wave per tile (few columns, contiguous rows) the matrix units win from k = 3 on when a row
+        //  has 16 lanes in the vector form, e.g. 1e7 x 100: k = 3 1.85 against 1.92 ms, k = 4 1.81 against 2.20)
+        int min_k = env_int("FUSE_MFMA_MIN_K", -1);
+        if (min_k < 0)
+            min_k = (n > 64 && mfma_wave_form(X, launch)) ? 3 : 5;
         const int64_t tile_bytes = (16 * ((n + 15) / 16 * 16 + 1) + (int64_t)(4 + 2 + std::max(nsides, 1)) * 272 + 128) * 8;
         if (ac == 3 && min_k > 0 && kd >= min_k && n >= 16 && tile_bytes <= 158 * 1024 &&
             mfma_pattern(prog, sides, nsides, vside))

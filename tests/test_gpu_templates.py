@@ -812,17 +812,21 @@ MLOGREG = [("main",)] + MLOG_Q + [("side", 1)] + MLOG_Q + [("rowsum",), ("mul",)
 TXXV = [("main",), ("main",), ("side", 0), ("matmult",), ("outerk",)]                     # t(X) (X V)
 
 
-@pytest.fixture(params=["vector", "matrix_units"])
+@pytest.fixture(params=["vector", "matrix_units", "matrix_units_blocks"])
 def rhs_form(request, monkeypatch):
-    """Both forms of t(X) (f(X V)) bodies: k-vectors on the vector ALUs (k butterflies per row), or the
-    two products on the fp64 matrix units (by default from 5 classes on, while 16 rows fit in LDS)."""
-    monkeypatch.setenv("FUSE_MFMA_MIN_K", "1" if request.param == "matrix_units" else "0")
+    """The forms of t(X) (f(X V)) bodies: k-vectors on the vector ALUs (k butterflies per row), or the
+    two products on the fp64 matrix units (by default from 3 or 5 classes on, while 16 rows fit in LDS):
+    one wave per 16-row tile for contiguous matrices of at most 112 columns, a block per tile otherwise
+    ("matrix_units_blocks" takes the block form for the narrow matrices too)."""
+    monkeypatch.setenv("FUSE_MFMA_MIN_K", "0" if request.param == "vector" else "1")
+    if request.param == "matrix_units_blocks":
+        monkeypatch.setenv("FUSE_MFMA_WAVE_FORM", "0")
     return request.param
 
 
 @pytest.mark.parametrize("shape", [(1, 1, 1), (70, 10, 3), (333, 100, 4), (129, 101, 2), (64, 1000, 2), (50, 784, 1),
                                    (500, 37, 16), (120, 784, 10), (33, 2048, 16), (40, 1000, 8), (17, 4096, 5), (9, 3000, 3),
-                                   (4100, 17, 7), (16, 16, 16), (15, 1199, 2)])
+                                   (4100, 17, 7), (16, 16, 16), (15, 1199, 2), (70001, 100, 6), (40003, 29, 9), (35000, 112, 16)])
 def test_row_matrix_rhs_chain_and_mlogreg_core(shape, rhs_form):
     """t(X) %*% (X %*% V) with an n x k right-hand side (Fig. 8g) and the multinomial logistic
     regression core H = t(X) (Q - P * rowSums(Q)), Q = P * (X V)  (Sec. 2.2, second example)."""
@@ -839,7 +843,9 @@ def test_row_matrix_rhs_chain_and_mlogreg_core(shape, rhs_form):
     got = host(F.fuse_row(TXXV, xd, sd, "col_t")).reshape(n, k)
     assert_close(got, plans.row_tx_xv_matrix(x, v), scale=scale, what="t(X)(XV)")
     if 16 <= n <= 1000:
-        assert F.last_kernel().startswith("fuse_row_mfma_") == (rhs_form == "matrix_units")
+        assert F.last_kernel().startswith("fuse_row_mfma_") == (rhs_form != "vector")
+        if n <= 112:
+            assert F.last_kernel().startswith("fuse_row_mfma_wave_") == (rhs_form == "matrix_units")
     got = host(F.fuse_row(MLOGREG, xd, sd, "col_t")).reshape(n, k)
     assert_close(got, plans.mlogreg_core(x, v, p), scale=2 * k * scale, what="mlogreg core")
     assert_close(got, unfused.row_dense(MLOGREG, x, [("rhs", v), ("kvec", p)], "col_t"), scale=2 * k * scale,
