@@ -10,6 +10,11 @@ inputs).  Dense inputs are drawn on the device (torch.rand), sparse patterns by 
 generators of workloads/; results are not compared with the oracle here (tests/ does that at
 sizes the oracle can handle), only checked to be finite.
 
+Two more groups follow the end-to-end experiments: "classes" is the shape of the class-count
+experiment (Sec. 5.4: 1e7 x 100 dense, t(X)(XV) and the multinomial logistic regression core of
+Sec. 2.2 for k = 2 .. 16 classes), "narrow" is Row t(X)(Xv) on the narrow dense matrices of Table 2
+(1e8 x 10 scaled to 1e7 x 10, and 29 columns as in Airline78).
+
     python bench_sweep.py [--only cell,row] [--max-rows 1000000] [--iters 7]
 """
 import argparse
@@ -21,7 +26,7 @@ import numpy as np
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--only", default="cell,cell_sparse,magg,magg_sparse,row,row_sparse,row_rhs,outer")
+    ap.add_argument("--only", default="cell,cell_sparse,magg,magg_sparse,row,row_sparse,row_rhs,outer,classes,narrow")
     ap.add_argument("--max-rows", type=int, default=1_000_000)
     ap.add_argument("--iters", type=int, default=7)
     args = ap.parse_args()
@@ -121,6 +126,30 @@ def main():
             report("8h", "Outer sum(X*log(U t(V)+1e-15)) sparsity %g" % sp, [m, nc, r], us,
                    12 * nnz + 8 * r * nnz + 8 * r * m, nnz)
             del xs
+
+    if "narrow" in only:
+        for (m, nc) in ((10_000_000, 10), (14_000_000, 29)):
+            x = torch.randn(m, nc, dtype=torch.float64, device="cuda")
+            v = torch.randn(nc, dtype=torch.float64, device="cuda")
+            report("tab2", "Row t(X)(Xv) dense, narrow", [m, nc],
+                   timed(lambda: F.fuse_row(TXV, x, [("rowvec", v)], "col_t")), 8 * m * nc + 16 * nc)
+            del x
+
+    if "classes" in only:
+        m, nc = 10_000_000, 100
+        q = [("side", 1), ("main",), ("side", 0), ("matmult",), ("mul",)]
+        mlogreg = [("main",)] + q + [("side", 1)] + q + [("rowsum",), ("mul",), ("sub",), ("outerk",)]
+        x = torch.randn(m, nc, dtype=torch.float64, device="cuda")
+        for k in (2, 4, 8, 16):
+            vk = torch.randn(nc, k, dtype=torch.float64, device="cuda")
+            p = torch.rand(m, k, dtype=torch.float64, device="cuda")
+            report("sec5.4", "Row t(X)(XV) dense, k=%d" % k, [m, nc],
+                   timed(lambda: F.fuse_row(TXXV, x, [("rhs", vk)], "col_t")), 8 * m * nc + 16 * nc * k)
+            report("sec5.4", "Row t(X)(Q - P*rowSums(Q)), Q = P*(XV), k=%d" % k, [m, nc],
+                   timed(lambda: F.fuse_row(mlogreg, x, [("rhs", vk), ("kvec", p)], "col_t")),
+                   8 * m * nc + 8 * m * k + 16 * nc * k)
+            del p
+        del x
 
 
 if __name__ == "__main__":
