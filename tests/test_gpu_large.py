@@ -133,3 +133,49 @@ def test_dense_beyond_2_31_elements():
     assert np.array_equal(out, exp)
     del x, y
     torch.cuda.empty_cache()
+
+
+def test_narrow_dense_beyond_2_31_elements():
+    """Narrow contiguous matrices with more than 2^31 elements: the dense Row skeleton with its rows staged
+    through shared memory (50 columns) and the one-wave-per-tile matrix-unit form of t(X) %*% (X %*% V)
+    (100 columns); integer-valued inputs, so every expected value is exact."""
+    import torch
+    import paper_1801_00829_amd as F
+    free, _ = torch.cuda.mem_get_info()
+    if free < 40 * 2**30:
+        pytest.skip("needs 40 GiB of free device memory")
+    txv = [("main",), ("side", 0), ("dot",), ("main",), ("mul",)]
+    txxv = [("main",), ("main",), ("side", 0), ("matmult",), ("outerk",)]
+    for (m, n) in ((44_000_000, 50), (22_000_000, 100)):
+        assert m * n > 2**31
+        print("narrow large", m, n, flush=True)
+        x = torch.ones(m, n, dtype=torch.float64, device="cuda")
+        r5, c5 = 2**31 // n, (2**31) % n
+        x[-1, -1] = 3.0                               # the very last element must be seen exactly once
+        x[r5, c5] = 5.0                               # and the one at flat index 2^31
+        # t(X) %*% (X %*% v) with v = 1: q_i = n except in the two marked rows
+        F.cache_clear()
+        v = torch.ones(n, dtype=torch.float64, device="cuda")
+        out = F.fuse_row(txv, x, [("rowvec", v)], "col_t").cpu().numpy()
+        if n == 50:
+            assert "#define FUSE_LDSX 1" in F.last_source()
+        q_last, q_mid = n + 2.0, n + 4.0
+        exp = np.full(n, float(m - 2) * n + q_last + q_mid)
+        exp[-1] += 2.0 * q_last
+        exp[c5] += 4.0 * q_mid
+        assert np.array_equal(out, exp)
+        # t(X) %*% (X %*% V), V[c][j] = c % 3 + j + 1
+        k = 4
+        vk = ((torch.arange(n, device="cuda") % 3)[:, None] + torch.arange(k, device="cuda")[None, :] + 1).to(torch.float64)
+        got = F.fuse_row(txxv, x, [("rhs", vk)], "col_t").cpu().numpy().reshape(n, k)
+        if n == 100:
+            assert F.last_kernel().startswith("fuse_row_mfma_wave_")
+        vh = vk.cpu().numpy()
+        s = vh.sum(0)
+        qm, ql = s + 4.0 * vh[c5], s + 2.0 * vh[n - 1]
+        exp = np.tile((m - 2) * s + qm + ql, (n, 1))
+        exp[c5] += 4.0 * qm
+        exp[n - 1] += 2.0 * ql
+        assert np.array_equal(got, exp)
+        del x
+        torch.cuda.empty_cache()
