@@ -341,17 +341,22 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
     // travelling tile, V and the running sums (0.93 / 1.18 - 1.45 against 0.95 / 1.0 - 1.1): the block form stays.
     if (mfma_wave_form(X, launch)) {
         const int64_t lds = (16 * np + 16 * 17) * 8;
-        // waves per SIMD the registers are budgeted for: two (256 registers each), or one when the body holds
-        // per-row k-vector sides of 8 and more classes next to V, the running sums and the travelling tile
-        // (1e7 x 100, multinomial logistic regression core: k = 8 2.2 against 2.4 ms, k = 16 2.5 against 5.9 ms)
+        // Bodies with per-row k-vector sides hold k-vectors next to V, the running sums and the travelling tile:
+        // for them the next tile starts travelling only after the generated code has run (its registers are free
+        // for the body), and from 13 classes on the registers are budgeted for one wave per SIMD (512) instead of
+        // two (256 each).  1e7 x 100, multinomial logistic regression core, early / late fetch: k = 8 2.42 / 1.67 ms
+        // (one wave per SIMD: 2.22 / 2.15), k = 12 3.77 / 2.19 (2.32 / 2.19), k = 16 5.90 / 3.16 (2.45 / 2.29).
         bool kvec_side = false;
         for (int q = 0; q < nsides; ++q)
             kvec_side = kvec_side || (prog.side_used[q] && sides[q].kind == FUSE_SIDE_KVEC);
         int wpe = env_int("FUSE_MFMA_WPE", 0);
         if (wpe != 1 && wpe != 2)
-            wpe = (kvec_side && kd >= 8) ? 1 : 2;
+            wpe = (kvec_side && kd > 12) ? 1 : 2;
+        int late = env_int("FUSE_MFMA_FETCH_LATE", -1);
+        if (late != 0 && late != 1)
+            late = kvec_side ? 1 : 0;
         const std::string key = std::string("rowmfmaw|") + pkey + "|" + side_key(sides, nsides) + "|n" + std::to_string(n) +
-                                "nt" + std::to_string(env_int("FUSE_NT", 1)) + "e" + std::to_string(wpe);
+                                "nt" + std::to_string(env_int("FUSE_NT", 1)) + "e" + std::to_string(wpe) + "l" + std::to_string(late);
         std::shared_ptr<Plan> plan;
         int rc = rt.plan(key, "fuse_row_mfma_wave", [&](const std::string &name) {
             std::string s = kSrcArgs;
@@ -359,7 +364,7 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
             s += kSrcCommon;
             s += "#define FUSE_KERNEL_NAME " + name + "\n";
             s += "#define FUSE_NCOLS " + std::to_string(n) + "\n#define FUSE_NP " + std::to_string(np) + "\n#define FUSE_NCT " +
-                 std::to_string(nct) + "\n#define FUSE_VSIDE " + std::to_string(vside) + "\n#define FUSE_WPE " + std::to_string(wpe) + "\n";
+                 std::to_string(nct) + "\n#define FUSE_VSIDE " + std::to_string(vside) + "\n#define FUSE_WPE " + std::to_string(wpe) + "\n#define FUSE_FETCH_LATE " + std::to_string(late) + "\n";
             s += side_tables(sides, nsides, prog.side_used);
             s += emit_row_body(prog);
             s += kSrcRowMfmaWave;
