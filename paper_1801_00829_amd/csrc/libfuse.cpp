@@ -345,7 +345,8 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
         // for them the next tile starts travelling only after the generated code has run (its registers are free
         // for the body), and from 13 classes on the registers are budgeted for one wave per SIMD (512) instead of
         // two (256 each).  1e7 x 100, multinomial logistic regression core, early / late fetch: k = 8 2.42 / 1.67 ms
-        // (one wave per SIMD: 2.22 / 2.15), k = 12 3.77 / 2.19 (2.32 / 2.19), k = 16 5.90 / 3.16 (2.45 / 2.29).
+        // (one wave per SIMD: 2.22 / 2.15), k = 12 3.77 / 2.19 (2.32 / 2.19), k = 16 5.90 / 3.16 (2.45 / 2.29); with the
+        // 4x4x4 products (k <= 8), on 3.2 GB: k = 8 1318 / 793 us, k = 5 777 / 753, k = 4 508 / 523, k = 2 491 / 523.
         bool kvec_side = false;
         for (int q = 0; q < nsides; ++q)
             kvec_side = kvec_side || (prog.side_used[q] && sides[q].kind == FUSE_SIDE_KVEC);
@@ -354,7 +355,7 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
             wpe = (kvec_side && kd > 12) ? 1 : 2;
         int late = env_int("FUSE_MFMA_FETCH_LATE", -1);
         if (late != 0 && late != 1)
-            late = kvec_side ? 1 : 0;
+            late = (kvec_side && kd > 4) ? 1 : 0;
         const std::string key = std::string("rowmfmaw|") + pkey + "|" + side_key(sides, nsides) + "|n" + std::to_string(n) +
                                 "nt" + std::to_string(env_int("FUSE_NT", 1)) + "e" + std::to_string(wpe) + "l" + std::to_string(late);
         std::shared_ptr<Plan> plan;
@@ -490,11 +491,14 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         int vside = -1;
         // (measured against the vector form: equal at k = 4 for n = 784, 2.6x faster at k = 8 for n = 256,
         //  3.2x at k = 10 for n = 784; slower for k = 4 at n = 100 and n = 1000)
-        //  with one wave per tile (few columns, contiguous rows) the matrix units win from k = 3 on when a row
-        //  has 16 lanes in the vector form, e.g. 1e7 x 100: k = 3 1.85 against 1.92 ms, k = 4 1.81 against 2.20)
+        //  with one wave per tile (few columns, contiguous rows; 4x4x4 products up to 8 classes) the matrix units
+        //  win earlier, the wider the rows are -- 3.2 GB, t(X)(XV) / logistic regression core, vector against
+        //  matrix units: n = 100 k = 2 510 / 530 against 486 / 500 us (k = 1: 463 / 469 against 480 / 493);
+        //  n = 64 k = 3 645 / 761 against 561 / 562 (k = 2: 487 / 509 against 638 / 546); n = 32 k = 4 824 / 956
+        //  against 740 / 720 (k = 3: 624 / 777 against 766 / 702); n = 16 k = 5 1102 / 1634 against 1169 / 1019)
         int min_k = env_int("FUSE_MFMA_MIN_K", -1);
         if (min_k < 0)
-            min_k = (n > 64 && mfma_wave_form(X, launch)) ? 3 : 5;
+            min_k = !mfma_wave_form(X, launch) ? 5 : n > 64 ? 2 : n > 32 ? 3 : n > 16 ? 4 : 5;
         const int64_t tile_bytes = (16 * ((n + 15) / 16 * 16 + 1) + (int64_t)(4 + 2 + std::max(nsides, 1)) * 272 + 128) * 8;
         if (ac == 3 && min_k > 0 && kd >= min_k && n >= 16 && tile_bytes <= 158 * 1024 &&
             mfma_pattern(prog, sides, nsides, vside))
