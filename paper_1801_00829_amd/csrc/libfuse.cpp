@@ -416,14 +416,24 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
         return fail(FUSE_EUNSUPPORTED, "internal: matrix-unit Row form chosen for a row tile that does not fit in LDS");
     const int BLOCK = 64 * NWAVE;
     const int64_t nld = (nvec + BLOCK / 16 - 1) / (BLOCK / 16);
+    // 4x4x4 products up to 4 classes (less padding, a higher instruction rate; FUSE_MFMA_M4: 0 never, 1 always).
+    // With more groups of 4 classes V's operands take one register pair per group and column step of the wave:
+    // 1e6 x 784, k = 10 spilled (4.6 against 1.6 ms); 1e6 x 256, k = 8: 365 / 588 against 443 / 469 us
+    // (t(X)(XV) / logistic regression core); k = 4: 1e6 x 784 1.17 / 1.19 against 1.61 / 1.66 ms, 3e6 x 128
+    // 0.67 / 0.72 against 0.91 / 0.97 ms.
+    int m4 = env_int("FUSE_MFMA_M4", -1);
+    if (m4 != 0 && m4 != 1)
+        m4 = kd <= 4 ? 1 : 0;
     const std::string key = std::string("rowmfma|") + pkey + "|" + side_key(sides, nsides) + "|v" + std::to_string(VEC) +
-                            "n" + std::to_string(nct) + "w" + std::to_string(NWAVE) + "nt" + std::to_string(env_int("FUSE_NT", 1));
+                            "n" + std::to_string(nct) + "w" + std::to_string(NWAVE) + "nt" + std::to_string(env_int("FUSE_NT", 1)) +
+                            "m" + std::to_string(m4);
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, "fuse_row_mfma", [&](const std::string &name) {
         std::string s = kSrcArgs;
         s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 1)) + "\n";
         s += kSrcCommon;
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
+        s += "#define FUSE_M4 " + std::to_string(m4) + "\n";
         s += "#define FUSE_NWAVE " + std::to_string(NWAVE) + "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_NP " + std::to_string(np) +
              "\n#define FUSE_NCT " + std::to_string(nct) + "\n#define FUSE_NLD " + std::to_string(nld) +
              "\n#define FUSE_VSIDE " + std::to_string(vside) + "\n";
@@ -491,6 +501,10 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         int vside = -1;
         // (measured against the vector form: equal at k = 4 for n = 784, 2.6x faster at k = 8 for n = 256,
         //  3.2x at k = 10 for n = 784; slower for k = 4 at n = 100 and n = 1000)
+        //  (that was with 16x16x4 products; with 4x4x4 products k = 4 wins at every width measured, on 3.2 GB,
+        //  t(X)(XV) / logistic regression core: n = 128 744 / 798 against 801 / 987 us, n = 256 584 / 613 against
+        //  871 / 992, n = 500 713 / 738 against 736 / 822, n = 784 626 / 665 against 1107 / 1149, n = 1000 639 / 676
+        //  against 886 / 879; k = 3 wins at n = 256 and 784 but loses at 128, 500 and 1000);
         //  with one wave per tile (few columns, contiguous rows; 4x4x4 products up to 8 classes) the matrix units
         //  win earlier, the wider the rows are -- 3.2 GB, t(X)(XV) / logistic regression core, vector against
         //  matrix units: n = 100 k = 2 510 / 530 against 486 / 500 us (k = 1: 463 / 469 against 480 / 493);
@@ -498,7 +512,7 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         //  against 740 / 720 (k = 3: 624 / 777 against 766 / 702); n = 16 k = 5 1102 / 1634 against 1169 / 1019)
         int min_k = env_int("FUSE_MFMA_MIN_K", -1);
         if (min_k < 0)
-            min_k = !mfma_wave_form(X, launch) ? 5 : n > 64 ? 2 : n > 32 ? 3 : n > 16 ? 4 : 5;
+            min_k = !mfma_wave_form(X, launch) ? 4 : n > 64 ? 2 : n > 32 ? 3 : n > 16 ? 4 : 5;
         const int64_t tile_bytes = (16 * ((n + 15) / 16 * 16 + 1) + (int64_t)(4 + 2 + std::max(nsides, 1)) * 272 + 128) * 8;
         if (ac == 3 && min_k > 0 && kd >= min_k && n >= 16 && tile_bytes <= 158 * 1024 &&
             mfma_pattern(prog, sides, nsides, vside))
