@@ -351,8 +351,11 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
         for (int q = 0; q < nsides; ++q)
             kvec_side = kvec_side || (prog.side_used[q] && sides[q].kind == FUSE_SIDE_KVEC);
         int wpe = env_int("FUSE_MFMA_WPE", 0);
-        if (wpe != 1 && wpe != 2)
-            wpe = (kvec_side && kd > 12) ? 1 : 2;
+        // Narrow tiles (n <= 32: 2 - 4 KB) leave a wave waiting on its own chain of LDS and MFMA latencies, and need
+        // few registers: four waves per SIMD there (3.2 GB, t(X)(XV): n = 16, k = 4 1129 -> 766 us, n = 32 758 -> 530;
+        // at n = 32 with k-vector sides of 16 classes it spilled: 2.6 against 1.1 ms)
+        if (wpe != 1 && wpe != 2 && wpe != 4 && wpe != 8)
+            wpe = (kvec_side && kd > 12) ? 1 : (n <= 32 && !(kvec_side && kd > 8)) ? 4 : 2;
         int late = env_int("FUSE_MFMA_FETCH_LATE", -1);
         if (late != 0 && late != 1)
             late = (kvec_side && kd > 4) ? 1 : 0;
