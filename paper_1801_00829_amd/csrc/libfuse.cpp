@@ -511,11 +511,12 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         //  with one wave per tile (few columns, contiguous rows; 4x4x4 products up to 8 classes) the matrix units
         //  win earlier, the wider the rows are -- 3.2 GB, t(X)(XV) / logistic regression core, vector against
         //  matrix units: n = 100 k = 2 510 / 530 against 486 / 500 us (k = 1: 463 / 469 against 480 / 493);
-        //  n = 64 k = 3 645 / 761 against 561 / 562 (k = 2: 487 / 509 against 638 / 546); n = 32 k = 4 824 / 956
-        //  against 740 / 720 (k = 3: 624 / 777 against 766 / 702); n = 16 k = 5 1102 / 1634 against 1169 / 1019)
+        //  n = 64 k = 3 645 / 761 against 561 / 562 (k = 2: 487 / 509 against 638 / 546); n = 32 k = 3 646 / 828
+        //  against 537 / 562 (k = 2: 500 / 502 against 521 / 524); n = 24 k = 3 780 / 979 against 699 / 625;
+        //  n = 16 k = 5 1029 / 1573 against 896 / 941 (k = 4: 724 / 995 against 793 / 896))
         int min_k = env_int("FUSE_MFMA_MIN_K", -1);
         if (min_k < 0)
-            min_k = !mfma_wave_form(X, launch) ? 4 : n > 64 ? 2 : n > 32 ? 3 : n > 16 ? 4 : 5;
+            min_k = !mfma_wave_form(X, launch) ? 4 : n > 64 ? 2 : n > 16 ? 3 : 5;
         const int64_t tile_bytes = (16 * ((n + 15) / 16 * 16 + 1) + (int64_t)(4 + 2 + std::max(nsides, 1)) * 272 + 128) * 8;
         if (ac == 3 && min_k > 0 && kd >= min_k && n >= 16 && tile_bytes <= 158 * 1024 &&
             mfma_pattern(prog, sides, nsides, vside))
