@@ -356,11 +356,22 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
         // at n = 32 with k-vector sides of 16 classes it spilled: 2.6 against 1.1 ms)
         if (wpe != 1 && wpe != 2 && wpe != 4 && wpe != 8)
             wpe = (kvec_side && kd > 12) ? 1 : (n <= 32 && !(kvec_side && kd > 8)) ? 4 : 2;
+        // Bodies with per-row k-vector sides of more than 12 classes: 4x4x4 products with V in LDS, shared by the four
+        // waves of a block, which frees V's registers for the body at two waves per SIMD (FUSE_MFMA_VLDS: 0 never,
+        // 1 whenever k > 8).  6.4 GB, logistic regression core, k = 16, against 16x16x4 with V in registers and one
+        // wave per SIMD: n = 100 1562 against 2083 us, n = 64 2176 against 2199, n = 32 2505 against 2694.  Elsewhere
+        // the B operand read from LDS per product costs more than the higher instruction rate gains (t(X)(XV),
+        // k = 9 / 12 / 16: n = 100 1591 / 1650 / 1533 against 1554 / 1580 / 1646 us, n = 64 1584 / 1626 / 1930
+        // against 1559 / 1619 / 1642, n = 32 1791 / 1849 / 2076 against 1551 / 1607 / 1698).
+        const int vlds_env = env_int("FUSE_MFMA_VLDS", -1);
+        const int vlds = vlds_env == 0 ? 0 : vlds_env == 1 ? (kd > 8) : (kvec_side && kd > 12);
+        if (vlds && env_int("FUSE_MFMA_WPE", 0) == 0)
+            wpe = 2;
         int late = env_int("FUSE_MFMA_FETCH_LATE", -1);
         if (late != 0 && late != 1)
             late = (kvec_side && kd > 4) ? 1 : 0;
         const std::string key = std::string("rowmfmaw|") + pkey + "|" + side_key(sides, nsides) + "|n" + std::to_string(n) +
-                                "nt" + std::to_string(env_int("FUSE_NT", 1)) + "e" + std::to_string(wpe) + "l" + std::to_string(late);
+                                "nt" + std::to_string(env_int("FUSE_NT", 1)) + "e" + std::to_string(wpe) + "l" + std::to_string(late) + "v" + std::to_string(vlds);
         std::shared_ptr<Plan> plan;
         int rc = rt.plan(key, "fuse_row_mfma_wave", [&](const std::string &name) {
             std::string s = kSrcArgs;
@@ -368,7 +379,7 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
             s += kSrcCommon;
             s += "#define FUSE_KERNEL_NAME " + name + "\n";
             s += "#define FUSE_NCOLS " + std::to_string(n) + "\n#define FUSE_NP " + std::to_string(np) + "\n#define FUSE_NCT " +
-                 std::to_string(nct) + "\n#define FUSE_VSIDE " + std::to_string(vside) + "\n#define FUSE_WPE " + std::to_string(wpe) + "\n#define FUSE_FETCH_LATE " + std::to_string(late) + "\n";
+                 std::to_string(nct) + "\n#define FUSE_VSIDE " + std::to_string(vside) + "\n#define FUSE_WPE " + std::to_string(wpe) + "\n#define FUSE_FETCH_LATE " + std::to_string(late) + "\n#define FUSE_VLDS " + std::to_string(vlds) + "\n";
             s += side_tables(sides, nsides, prog.side_used);
             s += emit_row_body(prog);
             s += kSrcRowMfmaWave;
@@ -387,10 +398,12 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
             return zero_fill(fn, out, n * kd, stream);
         const int64_t ntiles = (m + 15) / 16;
         // one-wave blocks: as many per CU as their LDS tiles allow, at most 8 (two per SIMD: their registers)
-        const int64_t wpc = std::max<int64_t>(1, std::min<int64_t>((158 * 1024) / lds, env_int("FUSE_MFMA_WAVES_PER_CU", 4 * wpe)));
-        const int64_t gx = std::max<int64_t>(1, std::min<int64_t>(ntiles, (int64_t)rt.num_cus() * wpc));
+        const int bw = vlds ? 4 : 1;          // waves per block
+        const int64_t lds_block = bw * lds + (vlds ? (n + 3) / 4 * 4 * 16 * 8 : 0);
+        const int64_t wpc = std::max<int64_t>(bw, std::min<int64_t>((160 * 1024) / lds_block * bw, env_int("FUSE_MFMA_WAVES_PER_CU", 4 * wpe)));
+        const int64_t gx = std::max<int64_t>(1, std::min<int64_t>((ntiles + bw - 1) / bw, (int64_t)rt.num_cus() * wpc / bw));
         Workspace ws;
-        if ((rc = rt.workspace(stream, (size_t)gx * (size_t)(n * kd), ws, g_err)))
+        if ((rc = rt.workspace(stream, (size_t)gx * bw * (size_t)(n * kd), ws, g_err)))
             return rc;
         fuse_kargs A;
         std::memset(&A, 0, sizeof A);
@@ -402,9 +415,10 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
         A.partials = ws.partials;
         A.ticket = ws.ticket;
         fill_side_args(A, sides, nsides);
-        if ((rc = rt.launch(fn.main, (unsigned)gx, 1, 64, stream, &A, sizeof A, g_err)))
+        if ((rc = rt.launch(fn.main, (unsigned)gx, 1, 64 * bw, stream, &A, sizeof A, g_err)))
             return rc;
-        return run_combine(fn, ws.partials, (int)gx, (int)(n * kd), out, stream);
+        // (a wave of the last block without a tile still writes its partial sums: zeros)
+        return run_combine(fn, ws.partials, (int)(gx * bw), (int)(n * kd), out, stream);
     }
     // waves per block (FUSE_MFMA_WAVES, default 8), fewer if the LDS next to the tile does not hold that many
     // partial products (16 x 17 doubles each)
