@@ -285,6 +285,17 @@ const char *fuse_last_error(void);
  * may be NULL. */
 int fuse_cache_stats(int64_t *hits, int64_t *misses, double *compile_ms);
 
+/* Compiled code objects can outlive the process: when the environment variable
+ * FUSE_CACHE_DIR names an existing directory, every body compiled by hipRTC is
+ * also written there (a file per kernel, named by a hash of the generated
+ * source, the compiler options and the hipRTC version; written under a
+ * temporary name and renamed), and a plan-cache miss first looks there.  A
+ * file that fails its length / checksum test is ignored and rewritten; an
+ * unwritable directory is not an error.  Returns how many misses since load /
+ * last clear were served from the directory (they count as misses above and
+ * add nothing to compile_ms). */
+int64_t fuse_cache_disk_hits(void);
+
 /* Drop every compiled body and free the workspaces.  The caller must have
  * synchronised all streams that libfuse work was enqueued on. */
 void fuse_cache_clear(void);

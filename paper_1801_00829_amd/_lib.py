@@ -76,6 +76,8 @@ def load():
     lib.fuse_cache_stats.argtypes = [i64p, i64p, dp]
     lib.fuse_cache_stats.restype = ci
     lib.fuse_cache_clear.restype = None
+    lib.fuse_cache_disk_hits.argtypes = []
+    lib.fuse_cache_disk_hits.restype = ctypes.c_int64
     lib.fuse_last_source.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
     lib.fuse_last_source.restype = ctypes.c_size_t
     lib.fuse_probe_copy.argtypes = [vp, vp, ctypes.c_int64, ci, vp]

@@ -393,6 +393,11 @@ def cache_clear():
     L.load().fuse_cache_clear()
 
 
+def cache_disk_hits():
+    """Plan-cache misses served from FUSE_CACHE_DIR since load / last clear."""
+    return int(L.load().fuse_cache_disk_hits())
+
+
 def last_source():
     lib = L.load()
     n = lib.fuse_last_source(None, 0)

@@ -1415,6 +1415,11 @@ int fuse_cache_stats(int64_t *hits, int64_t *misses, double *compile_ms)
     return FUSE_OK;
 }
 
+int64_t fuse_cache_disk_hits(void)
+{
+    return fuse::Runtime::get().disk_hits();
+}
+
 void fuse_cache_clear(void)
 {
     fuse::Runtime::get().clear();

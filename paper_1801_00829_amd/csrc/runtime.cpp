@@ -53,10 +53,87 @@ std::string Runtime::arch()
     return arch_;
 }
 
+namespace {
+
+// On-disk copies of compiled code objects (FUSE_CACHE_DIR): "FUSECO01", payload length, FNV-1a of the
+// payload, payload.  A file that does not check out is ignored and rewritten.
+const char kDiskMagic[8] = {'F', 'U', 'S', 'E', 'C', 'O', '0', '1'};
+
+uint64_t fnv1a(const char *d, size_t n)
+{
+    uint64_t h = 1469598103934665603ull;
+    for (size_t i = 0; i < n; ++i) {
+        h ^= (unsigned char)d[i];
+        h *= 1099511628211ull;
+    }
+    return h;
+}
+
+bool disk_read(const std::string &path, std::vector<char> &code)
+{
+    std::FILE *f = std::fopen(path.c_str(), "rb");
+    if (!f)
+        return false;
+    char magic[8];
+    uint64_t len = 0, sum = 0;
+    bool ok = std::fread(magic, 1, 8, f) == 8 && std::memcmp(magic, kDiskMagic, 8) == 0 &&
+              std::fread(&len, sizeof len, 1, f) == 1 && std::fread(&sum, sizeof sum, 1, f) == 1 && len > 0 &&
+              len < (1ull << 30);
+    if (ok) {
+        code.resize((size_t)len);
+        ok = std::fread(code.data(), 1, (size_t)len, f) == (size_t)len && std::fgetc(f) == EOF &&
+             fnv1a(code.data(), (size_t)len) == sum;
+    }
+    std::fclose(f);
+    if (!ok)
+        code.clear();
+    return ok;
+}
+
+void disk_write(const std::string &path, const std::vector<char> &code)
+{
+    // written under a name of its own and renamed: readers see a whole file or none
+    const std::string tmp = path + ".tmp" + std::to_string((unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count());
+    std::FILE *f = std::fopen(tmp.c_str(), "wb");
+    if (!f)
+        return;
+    const uint64_t len = code.size(), sum = fnv1a(code.data(), code.size());
+    const bool ok = std::fwrite(kDiskMagic, 1, 8, f) == 8 && std::fwrite(&len, sizeof len, 1, f) == 1 &&
+                    std::fwrite(&sum, sizeof sum, 1, f) == 1 && std::fwrite(code.data(), 1, code.size(), f) == code.size();
+    if (std::fclose(f) != 0 || !ok || std::rename(tmp.c_str(), path.c_str()) != 0)
+        std::remove(tmp.c_str());
+}
+
+}  // namespace
+
 int Runtime::compile(Plan &p, std::string &err)
 {
     const auto t0 = std::chrono::steady_clock::now();
     const std::string arch_opt = "--offload-arch=" + arch();
+    // -ffp-contract=off: a body rounds after every operator, exactly like the chain of
+    // basic operators it replaces (a*b+c is not silently turned into one fused
+    // multiply-add); the skeletons call fma() explicitly where they want one.
+    const char *opts[] = {arch_opt.c_str(), "-O3", "-std=c++17", "-Xclang", "-target-feature",
+                          "-Xclang", "-packed-fp32-ops", "-munsafe-fp-atomics", "-ffp-contract=off"};
+    // FUSE_CACHE_DIR: code objects are kept there across processes, named by the kernel and a hash of
+    // the source text, the options and the compiler's version
+    std::string disk_path;
+    if (const char *dir = std::getenv("FUSE_CACHE_DIR")) {
+        if (*dir) {
+            int major = 0, minor = 0;
+            (void)hiprtcVersion(&major, &minor);
+            std::string id = p.source + "\n";
+            for (const char *o : opts)
+                id += std::string(o) + " ";
+            id += "hiprtc " + std::to_string(major) + "." + std::to_string(minor);
+            disk_path = std::string(dir) + "/" + p.kernel_name + "-" + hash_hex(id) + ".co";
+            if (disk_read(disk_path, p.code)) {
+                std::lock_guard<std::mutex> lk(mu_);
+                ++disk_hits_;
+                return 0;
+            }
+        }
+    }
     hiprtcProgram prog;
     hiprtcResult r = hiprtcCreateProgram(&prog, p.source.c_str(), (p.kernel_name + ".hip").c_str(), 0,
                                          nullptr, nullptr);
@@ -64,11 +141,6 @@ int Runtime::compile(Plan &p, std::string &err)
         err = std::string("hiprtcCreateProgram: ") + hiprtcGetErrorString(r);
         return FUSE_ECOMPILE;
     }
-    // -ffp-contract=off: a body rounds after every operator, exactly like the chain of
-    // basic operators it replaces (a*b+c is not silently turned into one fused
-    // multiply-add); the skeletons call fma() explicitly where they want one.
-    const char *opts[] = {arch_opt.c_str(), "-O3", "-std=c++17", "-Xclang", "-target-feature",
-                          "-Xclang", "-packed-fp32-ops", "-munsafe-fp-atomics", "-ffp-contract=off"};
     r = hiprtcCompileProgram(prog, (int)(sizeof opts / sizeof opts[0]), opts);
     if (r != HIPRTC_SUCCESS) {
         size_t n = 0;
@@ -85,6 +157,8 @@ int Runtime::compile(Plan &p, std::string &err)
     p.code.resize(n);
     hiprtcGetCode(prog, p.code.data());
     hiprtcDestroyProgram(&prog);
+    if (!disk_path.empty())
+        disk_write(disk_path, p.code);
     const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     std::lock_guard<std::mutex> lk(mu_);
     compile_ms_ += ms;
@@ -229,6 +303,12 @@ void Runtime::stats(int64_t *hits, int64_t *misses, double *ms)
         *ms = compile_ms_;
 }
 
+int64_t Runtime::disk_hits()
+{
+    std::lock_guard<std::mutex> lk(mu_);
+    return disk_hits_;
+}
+
 void Runtime::clear()
 {
     std::lock_guard<std::mutex> lk(mu_);
@@ -248,7 +328,7 @@ void Runtime::clear()
     for (void *p : retired_)
         (void)hipFree(p);
     retired_.clear();
-    hits_ = misses_ = 0;
+    hits_ = misses_ = disk_hits_ = 0;
     compile_ms_ = 0.0;
 }
 

@@ -80,6 +80,7 @@ public:
 
     int num_cus();
     void stats(int64_t *hits, int64_t *misses, double *ms);
+    int64_t disk_hits();      // code objects taken from FUSE_CACHE_DIR instead of being compiled
     void clear();
 
     static std::string hash_hex(const std::string &s);
@@ -95,7 +96,7 @@ private:
     std::map<int, int> cus_;
     std::map<std::pair<hipFunction_t, int>, int> resident_;
     std::string arch_;
-    int64_t hits_ = 0, misses_ = 0;
+    int64_t hits_ = 0, misses_ = 0, disk_hits_ = 0;
     double compile_ms_ = 0.0;
 };
 

@@ -988,3 +988,25 @@ def test_row_body_with_the_most_reductions_and_stages():
         got = host(F.fuse_row(nested, to_dev(x), [], agg))
         assert_close(got, unfused.row_dense(nested, x, [], agg), tol=1e-9, what="five stages " + agg)
     assert "#define FUSE_NSTAGE 5" in F.last_source()
+
+
+def test_code_object_from_the_cache_directory_runs(tmp_path, monkeypatch):
+    """A body compiled in an earlier life of the in-memory plan cache is loaded from FUSE_CACHE_DIR and
+    gives the same bits."""
+    import paper_1801_00829_amd as F
+    monkeypatch.setenv("FUSE_CACHE_DIR", str(tmp_path))
+    rng = np.random.default_rng(99)
+    x, y = rng.normal(size=(2, 300, 77))
+    v = rng.normal(size=77)
+    cell = [("main",), ("side", 0), ("mul",), ("const", 0.987654321), ("add",), ("abs",)]
+    row = [("main",), ("side", 0), ("dot",), ("main",), ("mul",)]
+    xd, yd, vd = to_dev(x), to_dev(y), to_dev(v)
+    F.cache_clear()
+    first = host(F.fuse_cell(cell, xd, [("matrix", yd)], "full")), host(F.fuse_row(row, xd, [("rowvec", vd)], "col_t"))
+    assert F.cache_disk_hits() == 0 and len(os.listdir(tmp_path)) == 2
+    F.cache_clear()
+    again = host(F.fuse_cell(cell, xd, [("matrix", yd)], "full")), host(F.fuse_row(row, xd, [("rowvec", vd)], "col_t"))
+    assert F.cache_disk_hits() == 2 and F.cache_stats()[2] == 0.0
+    assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
+    assert_close(again[0], unfused.cell(cell, x, [("matrix", y)], "full"), scale=np.abs(x * y + 0.987654321).sum(), what="cached cell")
+    F.cache_clear()

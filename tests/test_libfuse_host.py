@@ -21,11 +21,11 @@ def F():
 
 def test_library_exports_every_declared_symbol(F):
     hdr = open(os.path.join(ROOT, "include", "fuse.h")).read()
-    declared = set(re.findall(r"^(?:int|void|size_t|const char \*)\s*\*?(fuse_\w+)\(", hdr, flags=re.M))
+    declared = set(re.findall(r"^(?:int|int64_t|void|size_t|const char \*)\s*\*?(fuse_\w+)\(", hdr, flags=re.M))
     assert {"fuse_cell", "fuse_magg", "fuse_row", "fuse_outer", "fuse_last_error", "fuse_cache_stats",
             "fuse_cache_clear", "fuse_prepare_cell", "fuse_prepare_magg", "fuse_prepare_row",
             "fuse_prepare_outer", "fuse_last_source", "fuse_last_kernel", "fuse_probe_copy",
-            "fuse_probe_read"} <= declared
+            "fuse_probe_read", "fuse_cache_disk_hits", "fuse_check_csr"} <= declared
     lib = ctypes.CDLL(F.lib_path())
     for name in declared:
         assert hasattr(lib, name), name
@@ -341,3 +341,39 @@ def test_cost_arithmetic_matches_the_papers_worked_example():
     nbytes = vals["rows"] * vals["cols"] * vals["bytes_per_cell"]
     assert bench.seconds_at(nbytes, vals["bandwidth_GBps"]) == vals["seconds"]
     assert bench.gbps(nbytes, vals["seconds"]) == vals["bandwidth_GBps"]
+
+
+def test_code_objects_persist_in_the_cache_directory(F, tmp_path, monkeypatch):
+    """FUSE_CACHE_DIR: a compiled body is written there and a later plan-cache miss (here: after clearing
+    the in-memory cache) takes it from there without compiling; a damaged file is ignored and rewritten."""
+    monkeypatch.setenv("FUSE_CACHE_DIR", str(tmp_path))
+    body = [("main",), ("const", 0.123456789), ("mul",), ("abs",), ("sqrt",)]
+    F.cache_clear()
+    F.prepare_cell(body, (64, 64), [], "full")
+    files = sorted(os.listdir(tmp_path))
+    assert len(files) == 1 and files[0].startswith(F.last_kernel() + "-") and files[0].endswith(".co")
+    hits, misses, ms = F.cache_stats()
+    assert (hits, misses) == (0, 1) and ms > 0 and F.cache_disk_hits() == 0
+    blob = open(os.path.join(tmp_path, files[0]), "rb").read()
+    assert blob[:8] == b"FUSECO01" and len(blob) > 1000
+    # a fresh in-memory cache: the miss is served from the directory
+    F.cache_clear()
+    F.prepare_cell(body, (64, 64), [], "full")
+    hits, misses, ms = F.cache_stats()
+    assert (hits, misses) == (0, 1) and ms == 0.0 and F.cache_disk_hits() == 1
+    # another body is another file
+    F.prepare_cell(body + [("neg",)], (64, 64), [], "full")
+    assert len(os.listdir(tmp_path)) == 2 and F.cache_disk_hits() == 1
+    # a truncated and a bit-flipped file are ignored, recompiled and rewritten whole
+    for damage in (lambda b: b[:len(b) // 2], lambda b: b[:200] + bytes([b[200] ^ 1]) + b[201:]):
+        open(os.path.join(tmp_path, files[0]), "wb").write(damage(blob))
+        F.cache_clear()
+        F.prepare_cell(body, (64, 64), [], "full")
+        assert F.cache_disk_hits() == 0 and F.cache_stats()[2] > 0
+        assert open(os.path.join(tmp_path, files[0]), "rb").read() == blob
+    # a directory that cannot be written is not an error
+    monkeypatch.setenv("FUSE_CACHE_DIR", str(tmp_path / "missing" / "dir"))
+    F.cache_clear()
+    F.prepare_cell(body, (64, 64), [], "full")
+    assert F.cache_disk_hits() == 0
+    F.cache_clear()
