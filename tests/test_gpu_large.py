@@ -164,18 +164,23 @@ def test_narrow_dense_beyond_2_31_elements():
         exp[-1] += 2.0 * q_last
         exp[c5] += 4.0 * q_mid
         assert np.array_equal(out, exp)
-        # t(X) %*% (X %*% V), V[c][j] = c % 3 + j + 1
-        k = 4
-        vk = ((torch.arange(n, device="cuda") % 3)[:, None] + torch.arange(k, device="cuda")[None, :] + 1).to(torch.float64)
-        got = F.fuse_row(txxv, x, [("rhs", vk)], "col_t").cpu().numpy().reshape(n, k)
-        if n == 100:
+        # t(X) %*% (X %*% V), V[c][j] = c % 3 + j + 1; 4, 8 and 16 classes take the three forms of the products
+        for k in (4, 8, 16):
+            vk = ((torch.arange(n, device="cuda") % 3)[:, None] + torch.arange(k, device="cuda")[None, :] + 1).to(torch.float64)
+            got = F.fuse_row(txxv, x, [("rhs", vk)], "col_t").cpu().numpy().reshape(n, k)
             assert F.last_kernel().startswith("fuse_row_mfma_wave_")
-        vh = vk.cpu().numpy()
-        s = vh.sum(0)
-        qm, ql = s + 4.0 * vh[c5], s + 2.0 * vh[n - 1]
-        exp = np.tile((m - 2) * s + qm + ql, (n, 1))
-        exp[c5] += 4.0 * qm
-        exp[n - 1] += 2.0 * ql
-        assert np.array_equal(got, exp)
+            vh = vk.cpu().numpy()
+            s = vh.sum(0)
+            qm, ql = s + 4.0 * vh[c5], s + 2.0 * vh[n - 1]
+            exp = np.tile((m - 2) * s + qm + ql, (n, 1))
+            exp[c5] += 4.0 * qm
+            exp[n - 1] += 2.0 * ql
+            assert np.array_equal(got, exp), k
+            # the same through a body with a per-row k-vector side: W = P * Q with P = 1 in every entry
+            pk = torch.ones(m, k, dtype=torch.float64, device="cuda")
+            body = [("main",), ("side", 1), ("main",), ("side", 0), ("matmult",), ("mul",), ("outerk",)]
+            got = F.fuse_row(body, x, [("rhs", vk), ("kvec", pk)], "col_t").cpu().numpy().reshape(n, k)
+            assert np.array_equal(got, exp), ("k-vector side", k)
+            del pk
         del x
         torch.cuda.empty_cache()
