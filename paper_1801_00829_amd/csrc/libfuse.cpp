@@ -527,10 +527,15 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         //  matrix units: n = 100 k = 2 510 / 530 against 486 / 500 us (k = 1: 463 / 469 against 480 / 493);
         //  n = 64 k = 3 645 / 761 against 561 / 562 (k = 2: 487 / 509 against 638 / 546); n = 32 k = 3 646 / 828
         //  against 537 / 562 (k = 2: 500 / 502 against 521 / 524); n = 24 k = 3 780 / 979 against 699 / 625;
-        //  n = 16 k = 5 1029 / 1573 against 896 / 941 (k = 4: 724 / 995 against 793 / 896))
+        //  n = 16 k = 5 1029 / 1573 against 896 / 941 (k = 4: 724 / 995 against 793 / 896); after 25 calls, when
+        //  both forms have sped up: n = 16 k = 4 625 / 774 against 611 / 683 (k = 3: 534 / 670 against 600 / 665),
+        //  n = 64 k = 2 479 / 517 against 474 / 490, n = 32 k = 2 480 / 513 against 500 / 531, n = 100 k = 1
+        //  462 / 470 against 481 / 490; block form: n = 256 k = 3 615 / 661 against 516 / 511 and n = 784 k = 3
+        //  742 / 736 against 597 / 622, but n = 128 k = 3 570 / 644 against 659 / 734, n = 500 k = 4 630 / 672
+        //  against 676 / 723, n = 1000 k = 3 516 / 547 against 594 / 609: the rule for the block form stays at 4)
         int min_k = env_int("FUSE_MFMA_MIN_K", -1);
         if (min_k < 0)
-            min_k = !mfma_wave_form(X, launch) ? 4 : n > 64 ? 2 : n > 16 ? 3 : 5;
+            min_k = !mfma_wave_form(X, launch) ? 4 : n >= 48 ? 2 : n > 16 ? 3 : 4;
         const int64_t tile_bytes = (16 * ((n + 15) / 16 * 16 + 1) + (int64_t)(4 + 2 + std::max(nsides, 1)) * 272 + 128) * 8;
         if (ac == 3 && min_k > 0 && kd >= min_k && n >= 16 && tile_bytes <= 158 * 1024 &&
             mfma_pattern(prog, sides, nsides, vside))
