@@ -204,7 +204,8 @@ int fuse_magg_csr(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
  *                   logistic regression (Sec. 2.2, second example) is one such body too.
  *                   Limit of this build: ceil(n / 2048) * 2 * k <= 48 (n <= 2048 for k = 16).
  *                   From 2 to 5 classes on, depending on the number of columns (and up to about
- *                   1200 columns), this shape runs on the fp64 matrix units.
+ *                   1200 columns), this shape runs on the fp64 matrix units; so does a CSR main
+ *                   input that stores at least 15 % of its cells, from 5 classes on.
  * For CSR input the body must be sparse-safe (Sec. 2.2 "Template Types": a
  * sparse-safe template binds only to the non-zeros): every vector that is
  * aggregated, multiplied with a right-hand side or returned must be zero

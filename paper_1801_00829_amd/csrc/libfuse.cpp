@@ -323,13 +323,15 @@ bool mfma_wave_form(const fuse_dense *X, bool launch)
     return X->cols <= 112 && X->ld == X->cols && (!launch || aligned16(X->data)) && env_int("FUSE_MFMA_WAVE_FORM", 1) != 0;
 }
 
-int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense *X, const fuse_side *sides,
+// X: the dense main input, or nullptr with Xs the CSR main input (block form only: its rows are spread out
+// into the dense LDS tile).
+int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense *X, const fuse_csr *Xs, const fuse_side *sides,
                   int nsides, int vside, double *out, hipStream_t stream, bool launch)
 {
     Runtime &rt = Runtime::get();
-    const int64_t m = X->rows, n = X->cols;
+    const int64_t m = X ? X->rows : Xs->rows, n = X ? X->cols : Xs->cols;
     const int kd = prog.kdim;
-    const bool vec2 = (n % 2 == 0) && (X->ld % 2 == 0) && (!launch || aligned16(X->data));
+    const bool vec2 = X && (n % 2 == 0) && (X->ld % 2 == 0) && (!launch || aligned16(X->data));
     const int VEC = vec2 ? 2 : 1;
     const int64_t nct = (n + 15) / 16;                       // 16-column tiles
     const int64_t np = nct * 16 + 1;                         // odd LDS row pitch
@@ -339,7 +341,7 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
     // 1.3 / 1.7 against 3.7 / 5.4 ms, n = 32 0.94 / 1.36 against 2.1 / 2.9, n = 64 0.83 / 1.13 against 1.26 / 1.56,
     // n = 100 0.86 / 1.10 against 1.15 / 1.23; with 8 column tiles (n = 128) the registers no longer hold the
     // travelling tile, V and the running sums (0.93 / 1.18 - 1.45 against 0.95 / 1.0 - 1.1): the block form stays.
-    if (mfma_wave_form(X, launch)) {
+    if (X && mfma_wave_form(X, launch)) {
         const int64_t lds = (16 * np + 16 * 17) * 8;
         // Bodies with per-row k-vector sides hold k-vectors next to V, the running sums and the travelling tile:
         // for them the next tile starts travelling only after the generated code has run (its registers are free
@@ -441,9 +443,17 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
     int m4 = env_int("FUSE_MFMA_M4", -1);
     if (m4 != 0 && m4 != 1)
         m4 = kd <= 4 ? 1 : 0;
+    // CSR input: cells per thread that travel in registers (the mean row length and a third, over the threads of a row)
+    const int csrx = Xs != nullptr;
+    const int rp64 = Xs && Xs->rowptr_is64;
+    int cap = 1;
+    if (Xs) {
+        const double avg = m > 0 ? (double)Xs->nnz / (double)m : 1.0;
+        cap = (int)std::min<int64_t>(16, std::max<int64_t>(1, (int64_t)(avg * 1.34 / (BLOCK / 16)) + 1));
+    }
     const std::string key = std::string("rowmfma|") + pkey + "|" + side_key(sides, nsides) + "|v" + std::to_string(VEC) +
                             "n" + std::to_string(nct) + "w" + std::to_string(NWAVE) + "nt" + std::to_string(env_int("FUSE_NT", 1)) +
-                            "m" + std::to_string(m4);
+                            "m" + std::to_string(m4) + (csrx ? "csr" + std::to_string(rp64) + "c" + std::to_string(cap) : "");
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, "fuse_row_mfma", [&](const std::string &name) {
         std::string s = kSrcArgs;
@@ -451,6 +461,8 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
         s += kSrcCommon;
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
         s += "#define FUSE_M4 " + std::to_string(m4) + "\n";
+        s += "#define FUSE_CSRX " + std::to_string(csrx) + "\n#define FUSE_RP64 " + std::to_string(rp64) + "\n#define FUSE_CAP " +
+             std::to_string(cap) + "\n";
         s += "#define FUSE_NWAVE " + std::to_string(NWAVE) + "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_NP " + std::to_string(np) +
              "\n#define FUSE_NCT " + std::to_string(nct) + "\n#define FUSE_NLD " + std::to_string(nld) +
              "\n#define FUSE_VSIDE " + std::to_string(vside) + "\n";
@@ -482,10 +494,18 @@ int row_mfma_impl(const Program &prog, const std::string &pkey, const fuse_dense
         return rc;
     fuse_kargs A;
     std::memset(&A, 0, sizeof A);
-    A.x = X->data;
+    if (X) {
+        A.x = X->data;
+        A.ld = X->ld;
+    } else {
+        A.x = Xs->vals;
+        A.colidx = Xs->colidx;
+        A.rowptr = Xs->rowptr;
+        A.nnz = Xs->nnz;
+        A.ld = n;
+    }
     A.m = m;
     A.n = n;
-    A.ld = X->ld;
     A.out = out;
     A.partials = ws.partials;
     A.ticket = ws.ticket;
@@ -539,7 +559,7 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
         const int64_t tile_bytes = (16 * ((n + 15) / 16 * 16 + 1) + (int64_t)(4 + 2 + std::max(nsides, 1)) * 272 + 128) * 8;
         if (ac == 3 && min_k > 0 && kd >= min_k && n >= 16 && tile_bytes <= 158 * 1024 &&
             mfma_pattern(prog, sides, nsides, vside))
-            return row_mfma_impl(prog, pkey, X, sides, nsides, vside, out, stream, launch);
+            return row_mfma_impl(prog, pkey, X, nullptr, sides, nsides, vside, out, stream, launch);
     }
 
     // vector width: 16-byte loads need even strides and aligned bases
@@ -835,6 +855,20 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     if (rk == KIND_VK && ac != 3)
         return fail(FUSE_EDESC, "an OUTERK result needs FUSE_AGG_COL / FUSE_AGG_COL_T");
     const int64_t nacck = rk == KIND_VK ? kd : 1;           // running sums per column
+
+    // t(X) %*% f(X %*% V) over a matrix that stores a good part of its cells (Mnist-like: a quarter): the dense
+    // matrix-unit form, whose LDS tile is filled from the CSR rows; its time does not depend on the density, the
+    // lane-group form's is proportional to it (FUSE_MFMA_CSR_DENSITY: least stored share in percent, default 15;
+    // FUSE_MFMA_CSR_MIN_K: least number of classes, default 5, 0 = never)
+    {
+        int vside = -1;
+        const int min_k = env_int("FUSE_MFMA_CSR_MIN_K", 5);
+        const double share = (m > 0 && n > 0) ? 100.0 * (double)X->nnz / ((double)m * (double)n) : 0.0;
+        const int64_t tile_bytes = (16 * ((n + 15) / 16 * 16 + 1) + (int64_t)(4 + 2 + std::max(nsides, 1)) * 272 + 128) * 8;
+        if (ac == 3 && min_k > 0 && kd >= min_k && n >= 16 && tile_bytes <= 158 * 1024 &&
+            share >= (double)env_int("FUSE_MFMA_CSR_DENSITY", 15) && mfma_pattern(prog, sides, nsides, vside))
+            return row_mfma_impl(prog, prog.key, nullptr, X, sides, nsides, vside, out, stream, launch);
+    }
 
     // lanes per row (G) and register-resident cells per lane (C): C*G is the power of two that covers
     // the mean row length plus 1.5 standard deviations of a Poisson-like length (the few longer rows take

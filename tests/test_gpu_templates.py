@@ -899,6 +899,56 @@ def test_row_csr_matrix_rhs_on_all_patterns(k):
                      scale=max(absq.sum(1).max(initial=0.0) + k, 1.0), what="csr rowSums(Q) + rowSums(P)")
 
 
+@pytest.mark.parametrize("rowptr64", [False, True])
+@pytest.mark.parametrize("case", ["mnist_like", "skewed", "narrow_full", "ragged_tail"])
+def test_row_csr_matrix_rhs_through_the_matrix_units(case, rowptr64, monkeypatch):
+    """CSR matrices that store a good part of their cells (Mnist-like: a quarter) take the dense matrix-unit
+    form, whose LDS tile is filled from the CSR rows: rows longer and shorter than what travels in registers,
+    empty rows, a row count that is no multiple of the tile; against the oracle's evaluation over the stored
+    cells and against the lane-group form."""
+    import torch
+    import paper_1801_00829_amd as F
+    if case == "mnist_like":
+        shape, k = (3001, 784), 10
+        rp, ci, va = W.csr_bernoulli(*shape, 0.25, 301)
+    elif case == "skewed":                       # most rows 16 % full, a few 95 % full, every seventh empty
+        shape, k = (1500, 300), 7
+        rp, ci, va = W.csr_skewed(*shape, 0.16, 40, 0.95, 302)
+        lens = np.diff(rp)
+        keep_row = np.arange(shape[0]) % 7 != 0
+        keep = np.repeat(keep_row, lens)
+        rp2 = np.zeros(shape[0] + 1, np.int64)
+        np.cumsum(np.where(keep_row, lens, 0), out=rp2[1:])
+        rp, ci, va = rp2, ci[keep], va[keep]
+    elif case == "narrow_full":
+        shape, k = (4100, 17), 16
+        rp, ci, va = W.csr_bernoulli(*shape, 1.0, 303)
+    else:
+        shape, k = (33, 1100), 5
+        rp, ci, va = W.csr_bernoulli(*shape, 0.5, 304)
+    m, n = shape
+    rng = np.random.default_rng(92)
+    v, p = rng.normal(size=(n, k)), rng.uniform(size=(m, k))
+    x = ops.make_csr(rp, ci, va, shape)
+    rpd = torch.from_numpy(rp).to(torch.int64 if rowptr64 else torch.int32).cuda()
+    xd = F.Csr(rpd, torch.from_numpy(ci).cuda(), to_dev(va), shape)
+    sd, hs = [("rhs", to_dev(v)), ("kvec", to_dev(p))], [("rhs", v), ("kvec", p)]
+    ax = ops.make_csr(rp, ci, np.abs(va), shape)
+    absq = ops.csr_matmul_dense(ax, ax.vals, np.abs(v))
+    scale = max(ops.csr_t_matmul_dense(ax, ax.vals, absq).max(initial=0.0), 1e-300)
+    for expr, fac in ((TXXV, 1.0), (MLOGREG, 2.0 * k)):
+        print("row csr matrix units", case, shape, "k", k, "rowptr64", rowptr64, flush=True)
+        got = host(F.fuse_row(expr, xd, sd, "col_t")).reshape(n, k)
+        assert F.last_kernel().startswith("fuse_row_mfma_")
+        ref = unfused.row_csr(expr, x, hs, "col_t")
+        assert_close(got, ref, scale=fac * scale, what="csr matrix units")
+        monkeypatch.setenv("FUSE_MFMA_CSR_MIN_K", "0")
+        other = host(F.fuse_row(expr, xd, sd, "col_t")).reshape(n, k)
+        assert F.last_kernel().startswith("fuse_row_csr_")
+        monkeypatch.delenv("FUSE_MFMA_CSR_MIN_K")
+        assert_close(got, other, scale=fac * scale, what="csr matrix units against lane groups")
+
+
 def test_row_matrix_rhs_strided_sides_and_limits(rhs_form):
     import paper_1801_00829_amd as F
     from oracle import plans
