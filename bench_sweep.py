@@ -13,7 +13,8 @@ sizes the oracle can handle), only checked to be finite.
 Two more groups follow the end-to-end experiments: "classes" is the shape of the class-count
 experiment (Sec. 5.4: 1e7 x 100 dense, t(X)(XV) and the multinomial logistic regression core of
 Sec. 2.2 for k = 2 .. 16 classes), "narrow" is Row t(X)(Xv) on the narrow dense matrices of Table 2
-(1e8 x 10 scaled to 1e7 x 10, and 29 columns as in Airline78).  The "classes" points run 25 untimed calls
+(1e8 x 10 scaled to 1e7 x 10, and 29 columns as in Airline78), "mnist" the shape of Mnist8m (784
+columns, a quarter of the cells stored, 10 classes; 1e6 rows), sparse and dense.  The "classes" points run 25 untimed calls
 first: the matrix-unit kernels speed up over the first ~20 calls on an idle device (the paper's
 experiments are iterative algorithms that call an operator many times).
 
@@ -28,7 +29,7 @@ import numpy as np
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--only", default="cell,cell_sparse,magg,magg_sparse,row,row_sparse,row_rhs,outer,classes,narrow")
+    ap.add_argument("--only", default="cell,cell_sparse,magg,magg_sparse,row,row_sparse,row_rhs,outer,classes,narrow,mnist")
     ap.add_argument("--max-rows", type=int, default=1_000_000)
     ap.add_argument("--iters", type=int, default=7)
     args = ap.parse_args()
@@ -136,6 +137,26 @@ def main():
             report("tab2", "Row t(X)(Xv) dense, narrow", [m, nc],
                    timed(lambda: F.fuse_row(TXV, x, [("rowvec", v)], "col_t")), 8 * m * nc + 16 * nc)
             del x
+
+    if "mnist" in only:
+        # the shape of Mnist8m (Table 2: 784 columns, a quarter of the cells stored, 10 classes), 1e6 rows
+        m, nc, k = 1_000_000, 784, 10
+        q = [("side", 1), ("main",), ("side", 0), ("matmult",), ("mul",)]
+        mlogreg = [("main",)] + q + [("side", 1)] + q + [("rowsum",), ("mul",), ("sub",), ("outerk",)]
+        xs, nnz = dev_csr(m, nc, 0.25, 17)
+        vk = torch.randn(nc, k, dtype=torch.float64, device="cuda")
+        p = torch.rand(m, k, dtype=torch.float64, device="cuda")
+        report("tab2", "Row t(X)(XV), X sparse 0.25, k=10", [m, nc],
+               timed(lambda: F.fuse_row(TXXV, xs, [("rhs", vk)], "col_t"), warm=10), 12 * nnz + 4 * m, nnz)
+        report("tab2", "Row t(X)(Q - P*rowSums(Q)), Q = P*(XV), X sparse 0.25, k=10", [m, nc],
+               timed(lambda: F.fuse_row(mlogreg, xs, [("rhs", vk), ("kvec", p)], "col_t"), warm=10),
+               12 * nnz + 4 * m + 8 * m * k, nnz)
+        xd = torch.randn(m, nc, dtype=torch.float64, device="cuda")
+        report("tab2", "Row t(X)(XV) dense, k=10", [m, nc],
+               timed(lambda: F.fuse_row(TXXV, xd, [("rhs", vk)], "col_t"), warm=10), 8 * m * nc)
+        report("tab2", "Row t(X)(Q - P*rowSums(Q)), Q = P*(XV) dense, k=10", [m, nc],
+               timed(lambda: F.fuse_row(mlogreg, xd, [("rhs", vk), ("kvec", p)], "col_t"), warm=10), 8 * m * nc + 8 * m * k)
+        del xs, xd, p
 
     if "classes" in only:
         m, nc = 10_000_000, 100
