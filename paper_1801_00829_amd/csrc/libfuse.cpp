@@ -923,15 +923,32 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     const int64_t naccpad = cols_lds ? std::max<int64_t>(n * nacck, 1) : 1;
 
     const int nt = env_int("FUSE_CSR_NT", streaming ? 1 : 0);
+    // lane-group form: the rows are dealt to the blocks in pieces of FUSE_CSR_ILV steps of a block (default 1:
+    // 256 rows with 16 rows per wave and 16 waves), round-robin, when every block gets at least four pieces;
+    // otherwise (and with FUSE_CSR_ILV=0) every block takes one contiguous range balanced by rows + stored cells.
+    // 1e7 x 1000, 1e8 stored cells, t(X)(Xv), medians of 6 x 20 calls: contiguous ranges 231.8 us, pieces of
+    // 1 step 223.9, 2 steps 224.1, 8 steps 228.4; 1e6 x 1000 with a tenth stored 217 -> 202 us; 2e6 x 1000 with
+    // 1 % stored and 2000 rows 70 % full 289 -> 246 us; 2e6 x 1000 with 20 cells per row 93 -> 87 us.
+    int ilv = 0;
+    if (!streaming) {
+        const int ilv_env = env_int("FUSE_CSR_ILV", -1);          // set: taken as it is, also for small matrices
+        ilv = ilv_env >= 0 ? ilv_env : 1;
+        const int64_t rpi = (int64_t)(64 / G) * RS * (BLOCK / 64);
+        const int64_t gx_est = std::max<int64_t>(1, std::min<int64_t>((m + rpi - 1) / rpi,
+                                                                      (int64_t)rt.num_cus() * env_int("FUSE_CSR_BLOCKS_PER_CU", 1)));
+        if (ilv_env < 0 && m < 4 * gx_est * ilv * rpi)
+            ilv = 0;
+    }
     const std::string key = std::string("rowcsr|") + prog.key + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(ac) + (streaming ? "|stream" + std::to_string(SC) + "r" + std::to_string(need_rid)
                                                             : "|g" + std::to_string(G) + "c" + std::to_string(C) + "r" + std::to_string(RS)) + "b" +
                             std::to_string(BLOCK) + "p" + std::to_string(npad) + "a" + std::to_string(naccpad) + "s" + std::to_string(stage_rv) + (cols_global ? "G" : "") +
                             "w" + std::to_string(X->rowptr_is64 != 0) + std::to_string(m < (1LL << 30)) + "nt" +
-                            std::to_string(nt);
+                            std::to_string(nt) + "i" + std::to_string(ilv);
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, name_prefix, [&](const std::string &name) {
         std::string s = kSrcArgs;
+        s += "#define FUSE_ILV " + std::to_string(ilv) + "\n";
         // group form: plain (cached) loads, the register slots of neighbouring rows overlap in
         // memory, so lines are re-used from cache; streaming form: every cell is read once
         s += "#define FUSE_NT " + std::to_string(nt) + "\n";

@@ -390,11 +390,18 @@ def _csr_cases():
     yield "many_empty_rows", (rp2, ci[keep], va[keep]), (200, 64)
 
 
-@pytest.fixture(params=["groups", "stream"])
+@pytest.fixture(params=["groups", "groups_dealt", "stream"])
 def csr_mapping(request, monkeypatch):
     """Both CSR Row skeletons: a lane group per row, or waves streaming runs of whole rows
-    (by default chosen from the mean row length)."""
+    (by default chosen from the mean row length).  The lane-group form gives every block one
+    contiguous row range balanced by rows + stored cells ("groups"; the default for small matrices) or
+    deals the rows to the blocks round-robin in pieces of one or three block steps ("groups_dealt"; pieces
+    of one step are the default for large matrices)."""
     monkeypatch.setenv("FUSE_CSR_STREAM", "1" if request.param == "stream" else "0")
+    if request.param == "groups":
+        monkeypatch.setenv("FUSE_CSR_ILV", "0")
+    elif request.param == "groups_dealt":
+        monkeypatch.setenv("FUSE_CSR_ILV", "1" if request.node.name.count("1") % 2 else "3")
     return request.param
 
 
