@@ -26,7 +26,7 @@ ALL = ("cell", "magg", "row_dense", "row_csr", "outer")
 # the 1 GiB copy probe (x2.000 for FETCH_SIZE, x1.000 for WRITE_SIZE); the summary is
 # profiles/bench_all_templates_hbm_traffic.txt.  Reported as roofline.traffic.
 MEASURED_TRAFFIC_BYTES = {"cell": 24.07e6, "magg": 2400.13e6, "row_dense": 808.90e6,
-                          "row_csr": 1381.12e6, "outer": 4840.83e6}
+                          "row_csr": 1379.26e6, "outer": 4840.86e6}
 
 
 def seconds_at(nbytes, gbps_):
