@@ -117,6 +117,56 @@ def test_calls_on_two_streams_keep_their_own_workspaces():
             assert abs(float(outs[i][rep].cpu()[0]) - refs[i]) <= 1e-10 * abs(refs[i]), (i, rep)
 
 
+def test_full_aggregates_back_to_back_on_changing_inputs():
+    """The single-launch finish of a full aggregate reuses one workspace per stream: a block's partial
+    sums from the previous call are still there when the next call starts.  Forty calls back to back
+    on one stream, every one on different inputs and with as many blocks as the device has compute
+    units, must each give their own sum -- a partial that the block with the last ticket read before
+    its publisher's store had arrived would be the previous call's (a different number here)."""
+    import torch
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(4242)
+    m, n, nset = 2100, 1000, 8                                 # 16.8 MB per matrix: one tile run per block and more
+    xs = [rng.uniform(-1.0, 1.0, size=(m, n)) * (1.0 + 3.0 * i) for i in range(nset)]
+    y, z = rng.uniform(size=(m, n)), rng.uniform(size=(m, n))
+    cell = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+    magg = [[("main",), ("side", 0), ("mul",)], [("main",), ("side", 1), ("mul",)], [("main",), ("pow2",)]]
+    ref_cell = [plans.cell_sum_xyz(x, y, z)[0] for x in xs]
+    ref_magg = [plans.magg_xy_xz_xx(x, y, z) for x in xs]
+    scale_cell = [float(np.abs(x * y * z).sum()) for x in xs]
+    scale_magg = [np.array([np.abs(x * y).sum(), np.abs(x * z).sum(), (x * x).sum()]) for x in xs]
+    dx = [to_dev(x) for x in xs]
+    sides = dev_sides([("matrix", y), ("matrix", z)])
+    reps = 40
+    oc = torch.full((reps,), float("nan"), dtype=torch.float64, device="cuda")
+    om = torch.full((reps, 3), float("nan"), dtype=torch.float64, device="cuda")
+    torch.cuda.synchronize()
+    for rep in range(reps):
+        i = (rep * 3) % nset                                   # consecutive calls never share an input
+        F.fuse_cell(cell, dx[i], sides, "full", out=oc[rep:rep + 1])
+        F.fuse_magg(magg, dx[i], sides, out=om[rep])
+    gc, gm = host(oc), host(om)
+    for rep in range(reps):
+        i = (rep * 3) % nset
+        assert abs(gc[rep] - ref_cell[i]) <= TOL * scale_cell[i], ("cell", rep, i, gc[rep], ref_cell[i])
+        assert (np.abs(gm[rep] - ref_magg[i]) <= TOL * scale_magg[i]).all(), ("magg", rep, i, gm[rep], ref_magg[i])
+    # the same for the Outer full aggregate (its own finish after a different main loop)
+    w = W.make_workload("outer", 0.03)
+    xo, u, v = dev_csr(*w["X"]), to_dev(w["U"]), to_dev(w["V"])
+    oo = torch.full((12,), float("nan"), dtype=torch.float64, device="cuda")
+    refs = []
+    for rep in range(12):
+        f = 1.0 + 0.5 * rep
+        refs.append(plans.outer_sum_x_log_uv(ops.make_csr(*w["X"]), w["U"] * f, w["V"])[0])
+    uf = [to_dev(w["U"] * (1.0 + 0.5 * rep)) for rep in range(12)]
+    torch.cuda.synchronize()
+    for rep in range(12):
+        F.fuse_outer(w["expr"], xo, uf[rep], v, [], "full", out=oo[rep:rep + 1])
+    go = host(oo)
+    for rep in range(12):
+        assert abs(go[rep] - refs[rep]) <= TOL * abs(refs[rep]), ("outer", rep, go[rep], refs[rep])
+
+
 def test_step_of_five_operators_replays_from_a_hip_graph():
     """After a warm-up on the same stream (plans compiled and loaded, workspace allocated) the calls
     enqueue kernels only, so a whole step can be captured into a HIP graph and replayed without the
