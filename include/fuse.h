@@ -56,7 +56,8 @@ typedef enum {
     FUSE_ECOMPILE = -4,     /* hipRTC rejected the generated source                   */
     FUSE_ERUNTIME = -5,     /* a HIP runtime call failed                              */
     FUSE_ENOMEM = -6,       /* workspace allocation failed                            */
-    FUSE_EUNSUPPORTED = -7  /* valid request that this build does not implement       */
+    FUSE_EUNSUPPORTED = -7, /* valid request that this build does not implement       */
+    FUSE_ENOTREADY = -8     /* fuse_magg_noalloc: the operator is not compiled and loaded yet */
 } fuse_status;
 
 /* Aggregation variants of Table 1.  COL and COL_T produce the same n values
@@ -169,6 +170,26 @@ int fuse_cell(const fuse_expr *expr, const fuse_dense *X, const fuse_side *sides
  * body j (the k x 1 output).  1 <= k <= 16. */
 int fuse_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides,
               int nsides, double *out_k, void *stream);
+
+/* fuse_magg for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, result and summation order as
+ * fuse_magg (k = 1 is the full aggregate of fuse_cell), but the call never allocates or frees device
+ * memory and never compiles or loads code:
+ *   - the block partials and the arrival counter live in a file-scope device array of the library
+ *     (256 bytes + FUSE_NOALLOC_MAX_PARTIALS doubles, 64.25 KB, held by every GPU the library runs on
+ *     until the process ends) instead of the per-stream workspace; a call whose grid needs more
+ *     (number of blocks x k; at most 256 x 16 with the default launch shape) is FUSE_EUNSUPPORTED;
+ *   - the operator must already be compiled and loaded on the current device, i.e. fuse_magg must have
+ *     run once with the same descriptor, side kinds and 16-byte alignment of the pointers;
+ *     otherwise FUSE_ENOTREADY and nothing is enqueued;
+ *   - only the flat form: X and all matrix sides contiguous (ld = cols), sides MATRIX or SCALAR;
+ *     anything else is FUSE_EUNSUPPORTED.
+ * Each call enqueues a one-block kernel that clears the arrival counter, then the operator's kernel.
+ * All calls on one GPU share the one array: calls of this entry point that overlap on a GPU (different
+ * streams or host threads) race; calls on one stream are ordered and independent of each other. */
+#define FUSE_NOALLOC_MAX_PARTIALS 8192
+int fuse_magg_noalloc(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides,
+                      int nsides, double *out_k, void *stream);
 
 /* Cell and MAgg over a SPARSE main input (Fig. 8b / 8d; Sec. 5.2: the sparse
  * matrix X is the "sparse driver" that makes the whole operator sparse-safe).

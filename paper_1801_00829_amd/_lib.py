@@ -56,6 +56,7 @@ def load():
     vp, ci, i64p, dp = ctypes.c_void_p, ctypes.c_int, P(ctypes.c_int64), P(ctypes.c_double)
     lib.fuse_cell.argtypes = [P(Expr), P(Dense), P(Side), ci, ci, vp, vp]
     lib.fuse_magg.argtypes = [P(Expr), ci, P(Dense), P(Side), ci, vp, vp]
+    lib.fuse_magg_noalloc.argtypes = [P(Expr), ci, P(Dense), P(Side), ci, vp, vp]
     lib.fuse_row.argtypes = [P(Expr), P(Dense), P(CsrDesc), P(Side), ci, ci, vp, vp]
     lib.fuse_outer.argtypes = [P(Expr), P(CsrDesc), P(Dense), P(Dense), P(Side), ci, ci, vp, vp]
     lib.fuse_cell_csr.argtypes = [P(Expr), P(CsrDesc), P(Side), ci, ci, vp, vp]
@@ -68,7 +69,7 @@ def load():
     lib.fuse_prepare_outer.argtypes = [P(Expr), P(CsrDesc), P(Dense), P(Dense), P(Side), ci, ci]
     lib.fuse_check_csr.argtypes = [P(CsrDesc), vp]
     for f in (lib.fuse_check_csr, lib.fuse_cell_csr, lib.fuse_magg_csr, lib.fuse_prepare_cell_csr, lib.fuse_prepare_magg_csr,
-              lib.fuse_cell, lib.fuse_magg, lib.fuse_row, lib.fuse_outer, lib.fuse_prepare_cell,
+              lib.fuse_cell, lib.fuse_magg, lib.fuse_magg_noalloc, lib.fuse_row, lib.fuse_outer, lib.fuse_prepare_cell,
               lib.fuse_prepare_magg, lib.fuse_prepare_row, lib.fuse_prepare_outer):
         f.restype = ci
     lib.fuse_last_error.restype = ctypes.c_char_p

@@ -207,6 +207,20 @@ def fuse_magg(exprs, X, sides=(), out=None, stream=None):
     return out
 
 
+def fuse_magg_noalloc(exprs, X, sides, out, stream=None):
+    """C: fuse_magg_noalloc.  The caller brings `out` (k float64 values on the device): nothing is allocated."""
+    lib = L.load()
+    pairs = [_expr(e) for e in exprs]
+    ea = (L.Expr * len(pairs))(*[p[0] for p in pairs])
+    xd = _dense(X)
+    sa, ns = _sides(list(sides), xd.rows, xd.cols)
+    if out is None:
+        raise ValueError("fuse_magg_noalloc needs the caller's output tensor")
+    out = _out(out, len(pairs), X)
+    _check(lib.fuse_magg_noalloc(ea, len(pairs), ctypes.byref(xd), sa, ns, out.data_ptr(), _stream(stream)))
+    return out
+
+
 def fuse_cell_csr(expr, X, sides=(), agg="full", out=None, stream=None):
     """C: fuse_cell_csr.  X: Csr of device tensors; sparse-safe Cell body at the stored cells."""
     lib = L.load()

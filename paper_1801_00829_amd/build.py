@@ -9,7 +9,7 @@ LIB = os.path.join(HERE, "libfuse.so")
 ARCH = "gfx950"
 
 HOST_SOURCES = ["libfuse.cpp", "expr.cpp", "runtime.cpp"]
-DEVICE_SOURCES = ["probe.hip", "check.hip", "transpose.hip"]
+DEVICE_SOURCES = ["probe.hip", "check.hip", "transpose.hip", "noalloc.hip"]
 TEXT_DEPS = ["fuse_args.h", "skel_common.inc", "skel_cell.inc", "skel_row_dense.inc", "skel_row_csr.inc", "skel_row_csr_stream.inc", "skel_row_mfma.inc", "skel_row_mfma_wave.inc",
              "skel_outer.inc", "expr.h", "runtime.h"]
 

@@ -716,8 +716,10 @@ int row_dense_impl(const Program &prog, const std::string &pkey, const fuse_dens
 }
 
 // ------------------------------------------------------------------ cell / magg --
+// noalloc: the variant that may not allocate (fuse_magg_noalloc): the plan must be compiled and loaded
+// already, only the flat form runs, and the block partials go to the library's fixed device array.
 int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides, int nsides,
-              int agg, double *out, void *stream_, bool launch, bool is_magg)
+              int agg, double *out, void *stream_, bool launch, bool is_magg, bool noalloc = false)
 {
     g_err.clear();
     Runtime &rt = Runtime::get();
@@ -759,6 +761,9 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
             else if (sides[q].kind != FUSE_SIDE_SCALAR)
                 flat = false;
         }
+    if (!flat && noalloc)
+        return fail(FUSE_EUNSUPPORTED, "fuse_magg_noalloc: only contiguous inputs (ld = cols) with matrix and scalar "
+                                       "side inputs");
     if (!flat) {
         // 2-D form: the Cell body (or the k bodies of a MAgg) as a Row body without row aggregates
         Program rprog;
@@ -786,7 +791,11 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
                             side_key(sides, nsides) + "|agg" + std::to_string(ac) + "|v" + std::to_string(VEC) +
                             "u" + std::to_string(UNROLL) + "nt" + std::to_string(env_int("FUSE_NT", 1));
     std::shared_ptr<Plan> plan;
-    rc = rt.plan(key, is_magg ? "fuse_magg" : "fuse_cell", [&](const std::string &name) {
+    const char *not_ready = "fuse_magg_noalloc: this operator is not compiled and loaded on the current device yet; "
+                            "call fuse_magg once with the same descriptor, side kinds and pointer alignment first";
+    if (noalloc && !rt.find_plan(key, plan))
+        return fail(FUSE_ENOTREADY, not_ready);
+    rc = noalloc ? 0 : rt.plan(key, is_magg ? "fuse_magg" : "fuse_cell", [&](const std::string &name) {
         std::string s = kSrcArgs;
         s += "#define FUSE_NT " + std::to_string(env_int("FUSE_NT", 1)) + "\n";
         s += kSrcCommon;
@@ -807,7 +816,10 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
         return 0;
 
     Plan::Loaded fn;
-    if ((rc = rt.load(*plan, fn, g_err)))
+    if (noalloc) {
+        if (!rt.loaded(*plan, fn))
+            return fail(FUSE_ENOTREADY, not_ready);
+    } else if ((rc = rt.load(*plan, fn, g_err)))
         return rc;
     const int64_t N = m * n;
     if (N == 0)
@@ -824,7 +836,14 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
     if (env_int("FUSE_CELL_GRID", 0) > 0)
         gx = env_int("FUSE_CELL_GRID", 0);
     Workspace ws;
-    if ((rc = rt.workspace(stream, (size_t)gx * k, ws, g_err)))
+    if (noalloc) {
+        if ((size_t)gx * k > (size_t)FUSE_NOALLOC_MAX_PARTIALS)
+            return fail(FUSE_EUNSUPPORTED, "fuse_magg_noalloc: " + std::to_string(gx) + " blocks x " + std::to_string(k) +
+                                               " aggregates need more than the " + std::to_string(FUSE_NOALLOC_MAX_PARTIALS) +
+                                               " block partials of the fixed workspace");
+        if ((rc = noalloc_workspace(stream, ws, g_err)))
+            return rc;
+    } else if ((rc = rt.workspace(stream, (size_t)gx * k, ws, g_err)))
         return rc;
     fuse_kargs A;
     std::memset(&A, 0, sizeof A);
@@ -1400,6 +1419,12 @@ int fuse_magg(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
               double *out_k, void *stream)
 {
     return guarded([&] { return cell_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, out_k, stream, true, true); });
+}
+
+int fuse_magg_noalloc(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_side *sides, int nsides,
+                      double *out_k, void *stream)
+{
+    return guarded([&] { return cell_impl(exprs, k, X, sides, nsides, FUSE_AGG_FULL, out_k, stream, true, true, true); });
 }
 
 int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, const fuse_side *sides,

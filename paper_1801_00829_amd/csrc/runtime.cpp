@@ -203,6 +203,30 @@ int Runtime::load(Plan &p, Plan::Loaded &fn, std::string &err)
     return 0;
 }
 
+bool Runtime::find_plan(const std::string &key, std::shared_ptr<Plan> &out)
+{
+    std::lock_guard<std::mutex> lk(mu_);
+    auto it = plans_.find(key);
+    if (it == plans_.end())
+        return false;
+    ++hits_;
+    out = it->second;
+    return true;
+}
+
+bool Runtime::loaded(Plan &p, Plan::Loaded &fn)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess)
+        return false;
+    std::lock_guard<std::mutex> lk(p.mu);
+    auto it = p.per_device.find(dev);
+    if (it == p.per_device.end())
+        return false;
+    fn = it->second;
+    return true;
+}
+
 int Runtime::workspace(hipStream_t stream, size_t doubles, Workspace &ws, std::string &err)
 {
     int dev = 0;

@@ -69,8 +69,12 @@ public:
         return 0;
     }
 
+    // Look up `key` only: false when no plan with that key has been compiled (nothing is compiled here).
+    bool find_plan(const std::string &key, std::shared_ptr<Plan> &out);
     // Load (once per device) and return the functions of a plan on the current device.
     int load(Plan &p, Plan::Loaded &fn, std::string &err);
+    // The functions of a plan if it is already loaded on the current device (nothing is loaded here).
+    bool loaded(Plan &p, Plan::Loaded &fn);
     // Workspace of (current device, stream) with room for `doubles` partials.
     int workspace(hipStream_t stream, size_t doubles, Workspace &ws, std::string &err);
     // Workgroups of `block` threads of kernel `f` that one compute unit holds at once (>= 1).
@@ -99,6 +103,11 @@ private:
     int64_t hits_ = 0, misses_ = 0, disk_hits_ = 0;
     double compile_ms_ = 0.0;
 };
+
+// The fixed workspace of the entry point that allocates nothing (noalloc.hip): the current device's copy of
+// a file-scope device array, FUSE_NOALLOC_MAX_PARTIALS doubles of block partials behind a zeroed arrival
+// counter.  Enqueues one small kernel on `stream` that clears the counter.  0 on success.
+int noalloc_workspace(hipStream_t stream, Workspace &ws, std::string &err);
 
 // Launches the CSR structure check (check.hip); `bad` points to four device words, the first
 // three preset to all ones and the last to zero.  0 on success.
