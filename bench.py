@@ -2,15 +2,25 @@
 
 A step is one pass of the whole hot path: the five fused operators (Cell, MAgg,
 Row dense, Row CSR, Outer) on the benchmark workloads, inputs resident in HBM.
-Prints ONE JSON line: whole-step effective GB/s (algorithmic bytes of the five
-operators / step time), a per-template breakdown, the roofline of the dominant
-kernel, and the CPU oracle timed on a bounded sample.
+Prints ONE JSON line:
+  value      effective HBM GB/s of the step = bytes the five operators must move from HBM
+             (Cell, MAgg, Row: their inputs once; Outer: X, U and V once -- its compulsory bytes)
+             / step time.  Never above the HBM peak by construction.
+  templates  per operator: time per call, GB/s and fraction of the HBM peak by the same byte
+             model; for Outer stored cells per second and the fraction of the measured L2
+             gather ceiling instead (it is not HBM-bound).
+  roofline   the dominant kernel of the step against the bound that binds it.
+  gather_ceilings  fuse_probe_gather over tables resident in L2, in the memory-side cache
+             and in HBM: the ceilings that the Outer figures are set against.
+  cpu_baseline  the CPU oracle timed on the same workloads, all host threads and one.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--templates cell,magg,...] [--no-cpu-baseline]
+    python bench.py --sweep [groups]     timing sweep over the paper's micro-benchmark sizes instead (see sweep())
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -20,13 +30,24 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0      # MI355X published HBM3E peak
 ALL = ("cell", "magg", "row_dense", "row_csr", "outer")
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_all_templates_hbm_traffic.txt")
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at the full
-# workload sizes in this launch configuration, scaled by what the same counters read for
-# the 1 GiB copy probe (x2.000 for FETCH_SIZE, x1.000 for WRITE_SIZE); the summary is
-# profiles/bench_all_templates_hbm_traffic.txt.  Reported as roofline.traffic.
-MEASURED_TRAFFIC_BYTES = {"cell": 24.07e6, "magg": 2400.13e6, "row_dense": 808.90e6,
-                          "row_csr": 1379.26e6, "outer": 4840.86e6}
+
+def profile_traffic(path=TRAFFIC_PROFILE):
+    """HBM-side bytes per launch by kernel name, from the committed rocprofv3 --pmc summary
+    (lines `traffic <kernel> <fetched bytes> <written bytes>`, already scaled by the copy probe).
+    A kernel that is not in the summary (its code changed since the counters were collected)
+    has no entry: the benchmark then reports null instead of a stale figure."""
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                w = line.split()
+                if len(w) == 4 and w[0] == "traffic":
+                    out[w[1]] = (float(w[2]), float(w[3]))
+    except OSError:
+        pass
+    return out
 
 
 def seconds_at(nbytes, gbps_):
@@ -38,10 +59,11 @@ def gbps(nbytes, seconds):
     return nbytes / seconds / 1e9
 
 
-def _cpu_baseline(names, host):
-    """The CPU oracle, as it stands, on the host copies of the same workloads (full size)."""
+def _oracle_pass(names, host):
+    """One pass of the CPU oracle's unfused plans over the host copies of the workloads:
+    ({name: seconds}, {name: result})."""
     from oracle import ops, plans
-    total_bytes, total_s, parts, results = 0, 0.0, [], {}
+    secs, results = {}, {}
     for name in names:
         w = host[name]
         t0 = time.perf_counter()
@@ -55,16 +77,273 @@ def _cpu_baseline(names, host):
             r = plans.row_csr_tx_xv(ops.make_csr(*w["X"]), w["sides"][0][1])
         else:
             r = plans.outer_sum_x_log_uv(ops.make_csr(*w["X"]), w["U"], w["V"])
-        dt = time.perf_counter() - t0
-        total_bytes += w["bytes"]
-        total_s += dt
-        parts.append("%s %.2f s" % (name, dt))
+        secs[name] = time.perf_counter() - t0
         results[name] = r
+    return secs, results
+
+
+def _cpu_baseline_child(names):
+    """Child-process mode (started with OMP_NUM_THREADS=1 by the parent): draws the same workloads
+    and times one oracle pass; prints {"threads": .., "seconds": {name: s}}.  Touches no GPU."""
+    import workloads as W
+    from oracle import ops
+    host = {n: W.make_workload(n, 1.0) for n in names}
+    secs, _ = _oracle_pass(names, host)
+    print(json.dumps({"threads": ops.threads(), "seconds": secs}), flush=True)
+
+
+def _cpu_baseline(names, host, hbm_bytes):
+    """The CPU oracle, as it stands, on the host copies of the same workloads (full size): once with all
+    host threads (in this process) and once with one thread (a child process with OMP_NUM_THREADS=1)."""
+    from oracle import ops
+    secs, results = _oracle_pass(names, host)
+    total_bytes, total_s = sum(hbm_bytes[n] for n in names), sum(secs.values())
     base = {"value": round(gbps(total_bytes, total_s), 3), "unit": "GB/s", "cores": ops.threads(),
             "kind": "oracle", "seconds": round(total_s, 3),
             "sample": "the full workloads, one pass of the unfused operator-at-a-time plans (" +
-                      "; ".join(parts) + ")"}
+                      "; ".join("%s %.2f s" % (n, secs[n]) for n in names) + "); bytes as in `value`"}
+    try:
+        env = dict(os.environ, OMP_NUM_THREADS="1")
+        r = subprocess.run([sys.executable, os.path.abspath(__file__), "--cpu-baseline-child", ",".join(names)],
+                           env=env, capture_output=True, text=True, timeout=600)
+        one = json.loads(r.stdout.strip().splitlines()[-1])
+        s1 = sum(one["seconds"].values())
+        base["one_core"] = {"value": round(gbps(total_bytes, s1), 3), "unit": "GB/s", "cores": one["threads"],
+                            "seconds": round(s1, 3),
+                            "sample": "; ".join("%s %.2f s" % (n, one["seconds"][n]) for n in names)}
+    except Exception as e:                           # noqa: BLE001 - the one-thread figure is an extra
+        base["one_core"] = {"error": str(e)[:200]}
     return base, results
+
+
+SWEEP_GROUPS = ("cell", "cell_sparse", "magg", "magg_sparse", "row", "row_sparse", "row_rhs", "outer", "classes", "narrow",
+                "mnist", "cell_variants", "chain", "cell_sparse_forms", "outer_variants")
+
+
+def sweep(args):
+    """Timing sweep over the paper's operator micro-benchmarks (Sec. 5.2, Fig. 8a-8h) on one GPU -- not the
+    benchmark line.  Walks the sizes of Fig. 8 -- Cell, MAgg and Row on x * 10^3 matrices for x in {1e3, 1e4,
+    1e5, 1e6}, dense and with a sparse X (sparsity 0.1), Row with a 1e3 x 2 right-hand side, Outer on 2e4 x 2e4
+    with rank 100 over sparsities 1 .. 1e-4 -- and prints one JSON line per point: median call time (HIP events
+    on the launch stream), the algorithmic bytes of the fused operator and the resulting GB/s (stored cells per
+    second for sparse inputs).  Dense inputs are drawn on the device, sparse patterns by the seeded generators
+    of workloads/; results are only checked to be finite here (tests/ compares with the oracle).
+
+    Further groups: "classes" the class-count experiment (Sec. 5.4: 1e7 x 100 dense, t(X)(XV) and the multinomial
+    logistic regression core of Sec. 2.2 for k = 2 .. 16; 25 untimed calls first: the matrix-unit kernels speed up
+    over the first ~20 calls on an idle device), "narrow" Row t(X)(Xv) on the narrow matrices of Table 2, "mnist"
+    the shape of Mnist8m (784 columns, a quarter stored, 10 classes; 1e6 rows), "cell_variants" the four variants
+    of Cell at 100000 x 1000, "chain" the instruction-footprint expression of Sec. 5.3, "cell_sparse_forms" Cell
+    bodies over a sparse X that run in the flat form, "outer_variants" the four Outer variants at the benchmark shape.
+    """
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py --sweep needs a GPU")
+    import paper_1801_00829_amd as F
+    import workloads as W
+
+    only = set(SWEEP_GROUPS) if args.sweep == "all" else set(args.sweep.split(","))
+    for g in only:
+        if g not in SWEEP_GROUPS:
+            sys.exit("unknown sweep group %r (known: %s)" % (g, ", ".join(SWEEP_GROUPS)))
+    n = 1000
+    rows = [x for x in (1000, 10_000, 100_000, 1_000_000) if x <= args.max_rows]
+
+    def timed(fn, warm=2):
+        for _ in range(warm):
+            out = fn()
+        torch.cuda.synchronize()
+        evs = []
+        for _ in range(args.iters):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            out = fn()
+            b.record()
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+        assert bool(torch.isfinite(out).all()), "non-finite result"
+        return ts[len(ts) // 2]
+
+    def report(fig, what, shape, us, nbytes, nnz=None, extra=None):
+        rec = {"fig": fig, "op": what, "shape": shape, "us": round(us, 1), "bytes": int(nbytes),
+               "GBps": round(nbytes / us / 1e3, 1)}
+        if extra:
+            rec.update(extra)
+        if nnz is not None:
+            rec["nnz"] = int(nnz)
+            rec["Gnnz_per_s"] = round(nnz / us / 1e3, 2)
+        print(json.dumps(rec), flush=True)
+
+    def dev_csr(m, ncols, density, seed):
+        rp, ci, va = W.csr_bernoulli(m, ncols, density, seed)
+        t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(dt).cuda()
+        return F.Csr(t(rp, torch.int32), t(ci, torch.int32), t(va, torch.float64), (m, ncols)), int(rp[-1])
+
+    XYZ = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+    XY_XZ = [[("main",), ("side", 0), ("mul",)], [("main",), ("side", 1), ("mul",)]]
+    TXV = [("main",), ("side", 0), ("dot",), ("main",), ("mul",)]
+    TXXV = [("main",), ("main",), ("side", 0), ("matmult",), ("outerk",)]
+    LOGUV = [("main",), ("uvdot",), ("const", 1e-15), ("add",), ("log",), ("mul",)]
+
+    for m in rows:
+        dense = only & {"cell", "magg", "row", "row_rhs", "cell_sparse", "magg_sparse"}
+        if dense:
+            x = torch.rand(m, n, dtype=torch.float64, device="cuda")
+            y = torch.rand(m, n, dtype=torch.float64, device="cuda")
+            z = torch.rand(m, n, dtype=torch.float64, device="cuda")
+            v = torch.rand(n, dtype=torch.float64, device="cuda")
+            sd = [("matrix", y), ("matrix", z)]
+        if "cell" in only:
+            report("8a", "Cell sum(X*Y*Z) dense", [m, n], timed(lambda: F.fuse_cell(XYZ, x, sd, "full")), 24 * m * n)
+        if "magg" in only:
+            report("8c", "MAgg sum(X*Y), sum(X*Z) dense", [m, n], timed(lambda: F.fuse_magg(XY_XZ, x, sd)), 24 * m * n)
+        if "row" in only:
+            report("8e", "Row t(X)(Xv) dense", [m, n], timed(lambda: F.fuse_row(TXV, x, [("rowvec", v)], "col_t")),
+                   8 * m * n + 16 * n)
+        if "row_rhs" in only:
+            vk = torch.rand(n, 2, dtype=torch.float64, device="cuda")
+            report("8g", "Row t(X)(XV) dense, V 1e3x2", [m, n],
+                   timed(lambda: F.fuse_row(TXXV, x, [("rhs", vk)], "col_t")), 8 * m * n + 32 * n * 2)
+        if only & {"cell_sparse", "magg_sparse", "row_sparse"}:
+            xs, nnz = dev_csr(m, n, 0.1, 11)
+            if "cell_sparse" in only:
+                # sparse driver X, dense Y and Z read at the stored positions (8 + 4 + 2*8 bytes per stored cell)
+                report("8b", "Cell sum(X*Y*Z), X sparse 0.1", [m, n],
+                       timed(lambda: F.fuse_cell_csr(XYZ, xs, sd, "full")), 28 * nnz + 4 * m, nnz)
+            if "magg_sparse" in only:
+                report("8d", "MAgg sum(X*Y), sum(X*Z), X sparse 0.1", [m, n],
+                       timed(lambda: F.fuse_magg_csr(XY_XZ, xs, sd)), 28 * nnz + 4 * m, nnz)
+            if "row_sparse" in only:
+                report("8f", "Row t(X)(Xv), X sparse 0.1", [m, n],
+                       timed(lambda: F.fuse_row(TXV, xs, [("rowvec", v)], "col_t")), 12 * nnz + 4 * m + 16 * n, nnz)
+            del xs
+        if dense:
+            del x, y, z
+
+    if "outer" in only:
+        m = nc = 20_000
+        r = 100
+        u = torch.rand(m, r, dtype=torch.float64, device="cuda")
+        v = torch.rand(nc, r, dtype=torch.float64, device="cuda")
+        for sp in (1.0, 0.1, 0.01, 0.001, 0.0001):
+            if sp == 1.0:      # all cells stored
+                rp = (torch.arange(m + 1, dtype=torch.int64, device="cuda") * nc).to(torch.int32)
+                ci = torch.arange(nc, dtype=torch.int32, device="cuda").repeat(m)
+                xs, nnz = F.Csr(rp, ci, torch.rand(m * nc, dtype=torch.float64, device="cuda"), (m, nc)), m * nc
+            else:
+                xs, nnz = dev_csr(m, nc, sp, 13)
+            us = timed(lambda: F.fuse_outer(LOGUV, xs, u, v, [], "full"))
+            report("8h", "Outer sum(X*log(U t(V)+1e-15)) sparsity %g" % sp, [m, nc, r], us,
+                   12 * nnz + 8 * r * nnz + 8 * r * m, nnz)
+            del xs
+
+    if "narrow" in only:
+        for (m, nc) in ((10_000_000, 10), (14_000_000, 29)):
+            x = torch.randn(m, nc, dtype=torch.float64, device="cuda")
+            v = torch.randn(nc, dtype=torch.float64, device="cuda")
+            report("tab2", "Row t(X)(Xv) dense, narrow", [m, nc],
+                   timed(lambda: F.fuse_row(TXV, x, [("rowvec", v)], "col_t")), 8 * m * nc + 16 * nc)
+            del x
+
+    if "mnist" in only:
+        # the shape of Mnist8m (Table 2: 784 columns, a quarter of the cells stored, 10 classes), 1e6 rows
+        m, nc, k = 1_000_000, 784, 10
+        q = [("side", 1), ("main",), ("side", 0), ("matmult",), ("mul",)]
+        mlogreg = [("main",)] + q + [("side", 1)] + q + [("rowsum",), ("mul",), ("sub",), ("outerk",)]
+        xs, nnz = dev_csr(m, nc, 0.25, 17)
+        vk = torch.randn(nc, k, dtype=torch.float64, device="cuda")
+        p = torch.rand(m, k, dtype=torch.float64, device="cuda")
+        report("tab2", "Row t(X)(XV), X sparse 0.25, k=10", [m, nc],
+               timed(lambda: F.fuse_row(TXXV, xs, [("rhs", vk)], "col_t"), warm=10), 12 * nnz + 4 * m, nnz)
+        report("tab2", "Row t(X)(Q - P*rowSums(Q)), Q = P*(XV), X sparse 0.25, k=10", [m, nc],
+               timed(lambda: F.fuse_row(mlogreg, xs, [("rhs", vk), ("kvec", p)], "col_t"), warm=10),
+               12 * nnz + 4 * m + 8 * m * k, nnz)
+        xd = torch.randn(m, nc, dtype=torch.float64, device="cuda")
+        report("tab2", "Row t(X)(XV) dense, k=10", [m, nc],
+               timed(lambda: F.fuse_row(TXXV, xd, [("rhs", vk)], "col_t"), warm=10), 8 * m * nc)
+        report("tab2", "Row t(X)(Q - P*rowSums(Q)), Q = P*(XV) dense, k=10", [m, nc],
+               timed(lambda: F.fuse_row(mlogreg, xd, [("rhs", vk), ("kvec", p)], "col_t"), warm=10), 8 * m * nc + 8 * m * k)
+        del xs, xd, p
+
+    if "classes" in only:
+        m, nc = 10_000_000, 100
+        q = [("side", 1), ("main",), ("side", 0), ("matmult",), ("mul",)]
+        mlogreg = [("main",)] + q + [("side", 1)] + q + [("rowsum",), ("mul",), ("sub",), ("outerk",)]
+        x = torch.randn(m, nc, dtype=torch.float64, device="cuda")
+        for k in (2, 4, 8, 16):
+            vk = torch.randn(nc, k, dtype=torch.float64, device="cuda")
+            p = torch.rand(m, k, dtype=torch.float64, device="cuda")
+            report("sec5.4", "Row t(X)(XV) dense, k=%d" % k, [m, nc],
+                   timed(lambda: F.fuse_row(TXXV, x, [("rhs", vk)], "col_t"), warm=25), 8 * m * nc + 16 * nc * k)
+            report("sec5.4", "Row t(X)(Q - P*rowSums(Q)), Q = P*(XV), k=%d" % k, [m, nc],
+                   timed(lambda: F.fuse_row(mlogreg, x, [("rhs", vk), ("kvec", p)], "col_t"), warm=25),
+                   8 * m * nc + 8 * m * k + 16 * nc * k)
+            del p
+        del x
+
+    if "cell_variants" in only:
+        # the four variants of the Cell template (Table 1) on 100000 x 1000, body X*Y; and with vector sides X*c*r
+        m = 100_000
+        x = torch.rand(m, n, dtype=torch.float64, device="cuda")
+        y = torch.rand(m, n, dtype=torch.float64, device="cuda")
+        c = torch.rand(m, dtype=torch.float64, device="cuda")
+        rv = torch.rand(n, dtype=torch.float64, device="cuda")
+        xy = [("main",), ("side", 0), ("mul",)]
+        xcr = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+        for agg, outb in (("full", 8), ("row", 8 * m), ("col", 8 * n), ("none", 8 * m * n)):
+            report("tab1", "Cell X*Y %s_agg" % agg, [m, n], timed(lambda: F.fuse_cell(xy, x, [("matrix", y)], agg)),
+                   16 * m * n + outb)
+            report("tab1", "Cell X*c*r %s_agg (column- and row-vector sides)" % agg, [m, n],
+                   timed(lambda: F.fuse_cell(xcr, x, [("colvec", c), ("rowvec", rv)], agg)), 8 * m * n + 8 * m + 8 * n + outb)
+        del x, y
+
+    if "chain" in only:
+        # the expression of the instruction-footprint experiment (Sec. 5.3): sum(f(X / rowSums(X))) with f a chain of
+        # N scalar multiplications -- body size against time and compile time
+        m = 100_000
+        x = torch.rand(m, n, dtype=torch.float64, device="cuda") + 0.5
+        for nops in (1, 10, 31, 51, 101, 201):
+            body_ = [("main",), ("main",), ("rowsum",), ("div",)]
+            for q in range(nops):
+                body_ += [("const", 1.0 + 1e-3 * (q + 1)), ("mul",)]
+            h0, m0, ms0 = F.cache_stats()
+            us = timed(lambda: F.fuse_row(body_, x, [], "full"))
+            h1, m1, ms1 = F.cache_stats()
+            rec_extra = {"compile_ms": round(ms1 - ms0, 1)}
+            report("sec5.3", "Row sum(f(X/rowSums(X))), f = %d multiplications" % nops, [m, n], us, 8 * m * n, extra=rec_extra)
+        del x
+
+    if "cell_sparse_forms" in only:
+        # Cell bodies over a sparse X (sparsity 0.1, 1e6 x 1e3) that never look at the row: flat form over the cell arrays
+        m = min(1_000_000, args.max_rows)
+        xs, nnz = dev_csr(m, n, 0.1, 11)
+        rv = torch.rand(n, dtype=torch.float64, device="cuda")
+        report("8b", "Cell sum(X^2), X sparse 0.1", [m, n], timed(lambda: F.fuse_cell_csr([("main",), ("pow2",)], xs, [], "full")),
+               8 * nnz, nnz)
+        report("8b", "Cell colSums(X*v), X sparse 0.1", [m, n],
+               timed(lambda: F.fuse_cell_csr([("main",), ("side", 0), ("mul",)], xs, [("rowvec", rv)], "col")), 12 * nnz, nnz)
+        report("8b", "Cell X*v no_agg, X sparse 0.1", [m, n],
+               timed(lambda: F.fuse_cell_csr([("main",), ("side", 0), ("mul",)], xs, [("rowvec", rv)], "none")), 20 * nnz, nnz)
+        del xs
+
+    if "outer_variants" in only:
+        # the four variants of the Outer template (Table 1) at the benchmark shape: 1e5 x 1e5, 1e7 stored cells, rank 100;
+        # product variants with the weights of the ALS-CG update (Sec. 2.2, first example)
+        m = nc = 100_000
+        r = 100
+        xs, nnz = dev_csr(m, nc, 0.001, 13)
+        u = torch.rand(m, r, dtype=torch.float64, device="cuda")
+        v = torch.rand(nc, r, dtype=torch.float64, device="cuda")
+        alscg = [("main",), ("neq0",), ("uvdot",), ("mul",)]
+        gather = 12 * nnz + 8 * r * nnz + 8 * r * m
+        report("tab1", "Outer sum(X*log(U t(V)+1e-15)) full_agg", [m, nc, r], timed(lambda: F.fuse_outer(LOGUV, xs, u, v, [], "full")), gather, nnz)
+        report("tab1", "Outer X*log(U t(V)+1e-15) no_agg", [m, nc, r], timed(lambda: F.fuse_outer(LOGUV, xs, u, v, [], "none")), gather + 8 * nnz, nnz)
+        report("tab1", "Outer ((X!=0)*(U t(V))) V right_mm", [m, nc, r], timed(lambda: F.fuse_outer(alscg, xs, u, v, [], "right_mm")), gather + 8 * r * m, nnz)
+        report("tab1", "Outer t((X!=0)*(U t(V))) U left_mm", [m, nc, r], timed(lambda: F.fuse_outer(alscg, xs, u, v, [], "left_mm")), gather + 8 * r * nc, nnz)
+        del xs, u, v
+
 
 
 def main():
@@ -77,7 +356,16 @@ def main():
     ap.add_argument("--probe", action="store_true",
                     help="also launch the 1 GiB copy / read probes once (untimed): a transfer of known "
                          "size that calibrates profiler byte counters collected over this command")
+    ap.add_argument("--sweep", nargs="?", const="all", default=None, metavar="GROUPS",
+                    help="timing sweep over the paper's micro-benchmark sizes instead of the benchmark line "
+                         "(comma-separated groups, see sweep(); default all)")
+    ap.add_argument("--max-rows", type=int, default=1_000_000, help="--sweep: largest number of rows of the Fig. 8 groups")
+    ap.add_argument("--iters", type=int, default=7, help="--sweep: timed calls per point (median reported)")
+    ap.add_argument("--cpu-baseline-child", default=None, help=argparse.SUPPRESS)
     args = ap.parse_args()
+    if args.cpu_baseline_child is not None:
+        _cpu_baseline_child([n for n in args.cpu_baseline_child.split(",") if n])
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the fused operators are single-device kernels); "
                  "--gpus %d is not supported" % args.gpus)
@@ -85,6 +373,10 @@ def main():
     for n in names:
         if n not in ALL:
             sys.exit("unknown template %r" % n)
+
+    if args.sweep is not None:
+        sweep(args)
+        return
 
     import numpy as np
     import torch
@@ -109,7 +401,8 @@ def main():
     for name in names:
         t0 = time.perf_counter()
         w = W.make_workload(name, 1.0)
-        info[name] = {"bytes": int(w["bytes"]), "nnz": int(w.get("nnz", 0))}
+        # bytes: what the operator must move from HBM (its inputs once; for Outer X, U and V once)
+        info[name] = {"bytes": int(w.get("bytes_compulsory", w["bytes"])), "nnz": int(w.get("nnz", 0))}
         if name == "cell":
             x, s, out = dev(w["X"]), sides(w["sides"]), torch.empty(1, dtype=torch.float64, device="cuda")
             calls[name] = (lambda e=w["expr"], x=x, s=s, a=w["agg"], o=out: F.fuse_cell(e, x, s, a, out=o))
@@ -125,7 +418,8 @@ def main():
         else:
             x, u, v = csr(w["X"]), dev(w["U"]), dev(w["V"])
             out = torch.empty(1, dtype=torch.float64, device="cuda")
-            info[name]["bytes_compulsory"] = int(w["bytes_compulsory"])
+            info[name]["bytes_gather_model"] = int(w["bytes"])       # one V row per stored cell, U once per row
+            info[name]["rank"] = int(w["U"].shape[1])
             calls[name] = (lambda e=w["expr"], x=x, u=u, v=v, a=w["agg"], o=out: F.fuse_outer(e, x, u, v, [], a, out=o))
         host[name] = w
         outs[name] = out
@@ -235,6 +529,52 @@ def main():
                       "what": "fuse_probe_read over %d cold bytes, 2048 blocks, same event bracket" % (nb * 8)}
         del buf, evict
 
+    # ---- gather ceilings: whole rows of a table read at random (fuse_probe_gather, the V_j fetch of the
+    # Outer template without its arithmetic) from a table that fits one L2, one that fits the memory-side
+    # cache (the size of V) and one that fits neither; and from the V-sized table in the order of a panel
+    # walk (random inside a 5 MB window that moves through the table).  Stored cells per second of the
+    # Outer operator are set against these, not against the HBM peak.
+    ceilings = None
+    if "outer" in names:
+        r = info["outer"]["rank"]
+        cnt = 10_000_000
+        sink = torch.zeros(1, dtype=torch.float64, device="cuda")
+
+        def gather_rate(rows, idx):
+            table = torch.rand(rows, r, dtype=torch.float64, device="cuda")
+            ts = []
+            for k in range(7):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                F.probe_gather(table, idx, sink, 1024)
+                b.record()
+                ts.append((a, b))
+            torch.cuda.synchronize()
+            t = sorted(a.elapsed_time(b) for a, b in ts[2:])[len(ts[2:]) // 2] * 1e-3
+            return idx.numel() / t
+
+        def rnd(rows):
+            return torch.randint(0, rows, (cnt,), dtype=torch.int32, device="cuda")
+
+        row_bytes = 8 * r
+        sizes = {"l2_resident_2MB": 2_000_000 // row_bytes, "cache_resident_80MB": 80_000_000 // row_bytes,
+                 "hbm_resident_2GB": 2_000_000_000 // row_bytes}
+        ceilings = {"what": "fuse_probe_gather: %d random rows of %d bytes, 8 lanes per row, 4 rows in flight per group, "
+                            "1024 blocks; median of 5" % (cnt, row_bytes), "rows_per_s": {}, "GBps": {}}
+        for key, rows in sizes.items():
+            rate = gather_rate(rows, rnd(rows))
+            ceilings["rows_per_s"][key] = float("%.4g" % rate)
+            ceilings["GBps"][key] = round(rate * row_bytes / 1e9, 1)
+        rows, win = sizes["cache_resident_80MB"], 5_000_000 // row_bytes
+        nwin = rows // win
+        idx = torch.cat([torch.randint(q * win, (q + 1) * win, (cnt // nwin,), dtype=torch.int32, device="cuda")
+                         for q in range(nwin)])
+        rate = gather_rate(rows, idx)
+        ceilings["rows_per_s"]["80MB_in_5MB_windows"] = float("%.4g" % rate)
+        ceilings["GBps"]["80MB_in_5MB_windows"] = round(rate * row_bytes / 1e9, 1)
+        del idx
+
+    traffic = profile_traffic()
     templates = {}
     for name in names:
         ts = sorted(a.elapsed_time(b) for a, b in ev[name])           # milliseconds
@@ -243,19 +583,48 @@ def main():
              "min_us": round(ts[0] * 1e3, 2), "median_us": round(ts[len(ts) // 2] * 1e3, 2),
              "GBps": round(gbps(info[name]["bytes"], avg * 1e-3), 1)}
         e["frac_of_hbm_peak"] = round(e["GBps"] / HBM_PEAK_GBPS, 4)
-        e["traffic"] = MEASURED_TRAFFIC_BYTES.get(name)
+        tr = traffic.get(kernels[name])
+        e["traffic"] = None if tr is None else tr[0] + tr[1]
+        if tr is not None:
+            e["traffic_GBps"] = round(gbps(tr[0] + tr[1], avg * 1e-3), 1)
         if info[name]["nnz"]:
-            e["nnz_per_s"] = round(info[name]["nnz"] / (avg * 1e-3), 1)
-        if "bytes_compulsory" in info[name]:
-            e["GBps_compulsory_model"] = round(gbps(info[name]["bytes_compulsory"], avg * 1e-3), 1)
+            e["nnz_per_s"] = float("%.5g" % (info[name]["nnz"] / (avg * 1e-3)))
+        if name == "outer":
+            e["bound"] = "l2_gather"
+            e["bytes_gather_model"] = info[name]["bytes_gather_model"]
+            e["GBps_gather_model"] = round(gbps(info[name]["bytes_gather_model"], avg * 1e-3), 1)
+            e["frac_of_l2_gather_ceiling"] = round(e["nnz_per_s"] / ceilings["rows_per_s"]["l2_resident_2MB"], 4)
+            e["note"] = ("not HBM-bound: the step's HBM bytes are X, U and V once (GBps, frac_of_hbm_peak); the time goes "
+                         "into one V row per stored cell, served by L2 in the column-panel form -- see roofline")
+        else:
+            e["bound"] = "hbm"
+            e["meets_70pct_target"] = bool(e["frac_of_hbm_peak"] >= 0.70)
         if name == "cell" and cell_floor is not None:
             e["plain_read_floor"] = cell_floor
         templates[name] = e
     total_bytes = sum(info[n]["bytes"] for n in names)
     dominant = max(names, key=lambda n: templates[n]["avg_us"])
     d = templates[dominant]
+    if dominant == "outer":
+        # achieved / peak in bytes of V rows gathered per second (8r per stored cell on both sides)
+        row_bytes = 8 * info["outer"]["rank"]
+        peak = ceilings["rows_per_s"]["l2_resident_2MB"] * row_bytes / 1e9
+        ach = d["nnz_per_s"] * row_bytes / 1e9
+        roofline = {"bound": "l2_gather", "kernel": d["kernel"], "template": dominant, "achieved": round(ach, 1),
+                    "peak": round(peak, 1), "unit": "GB/s", "frac": round(ach / peak, 4), "traffic": d["traffic"],
+                    "note": "Outer is bound by the gather of one V row per stored cell, which its column panels serve from "
+                            "L2: achieved = stored cells/s x 8r bytes, peak = the rate fuse_probe_gather reaches on an "
+                            "L2-resident table in this run (gather_ceilings); against the HBM peak the same kernel stands at "
+                            "frac_of_hbm_peak of its compulsory bytes, and at traffic_GBps of the bytes its L2 misses move"}
+    else:
+        roofline = {"bound": "hbm", "kernel": d["kernel"], "template": dominant, "achieved": d["GBps"],
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(d["GBps"] / HBM_PEAK_GBPS, 4),
+                    "traffic": d["traffic"]}
+    hbm_bound = [n for n in names if n != "outer"]
     result = {
-        "metric": "effective HBM GB/s of one pass over the fused templates (algorithmic bytes / step time)",
+        "metric": "effective HBM GB/s of one pass over the five fused templates (bytes each operator must move from "
+                  "HBM -- its inputs once -- / step time); per-template fractions of the HBM peak and nnz/s for Outer "
+                  "in `templates`",
         "value": round(gbps(total_bytes, elapsed / K), 1), "unit": "GB/s", "n_gpus": 1, "steps": K,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f64", "data": "synthetic",
@@ -264,18 +633,16 @@ def main():
              "row_dense": "Row t(X)%*%(w*(X%*%v)) 1e6x100", "row_csr": "Row-CSR t(X)%*%(X%*%v) 1e7x1000 d=0.01",
              "outer": "Outer sum(X*log(U%*%t(V)+1e-15)) 1e5x1e5 d=0.001 r=100"}[n] for n in names),
             "seed": W.BASE_SEED},
-        "roofline": {"bound": "hbm", "kernel": d["kernel"], "template": dominant, "achieved": d["GBps"],
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(d["GBps"] / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant),
-                     "traffic_GBps": round(gbps(MEASURED_TRAFFIC_BYTES.get(dominant), d["avg_us"] * 1e-6), 1),
-                     "note": ("Outer: algorithmic bytes by the gather model (one V row per non-zero); frac > 1 means "
-                              "gathers served by L2 (column panels), see traffic") if dominant == "outer" else ""},
+        "frac_of_hbm_peak": round(gbps(total_bytes, elapsed / K) / HBM_PEAK_GBPS, 4),
+        "roofline": roofline,
         "templates": templates,
+        "below_70pct_of_hbm_peak": [n for n in hbm_bound if not templates[n]["meets_70pct_target"]],
+        "gather_ceilings": ceilings,
         "plan_cache": {"hits": hits, "misses": misses, "compile_ms": round(compile_ms, 1)},
         "hip_graph_replay": graph,
     }
     if not args.no_cpu_baseline:
-        base, refs = _cpu_baseline(names, host)
+        base, refs = _cpu_baseline(names, host, {n: info[n]["bytes"] for n in names})
         result["cpu_baseline"] = base
         # the same run also checks the GPU results against the oracle's
         errs = {}

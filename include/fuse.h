@@ -339,6 +339,14 @@ const char *fuse_last_kernel(void);
  * `sink` is one device double that is practically never written. */
 int fuse_probe_copy(double *dst, const double *src, int64_t n_doubles, int blocks, void *stream);
 int fuse_probe_read(const double *src, int64_t n_doubles, int blocks, double *sink, void *stream);
+/* A third measurement helper: reads `count` whole rows of a dense table (rows x row_doubles, leading
+ * dimension ld, all even, row_doubles <= 128, table 16-byte aligned) in the order idx[0..count) gives
+ * (device array; every entry must lie in [0, rows): like the CSR arrays it is trusted, not checked),
+ * 8 lanes per row and 4 rows in flight per group -- the V_j fetch of the Outer template without its
+ * arithmetic.  With random indices it gives the rate at which the device serves such row gathers from a
+ * table of that size, which is the ceiling the Outer template is measured against. */
+int fuse_probe_gather(const double *table, int64_t rows, int64_t row_doubles, int64_t ld,
+                      const int32_t *idx, int64_t count, int blocks, double *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -7,5 +7,5 @@ memory and streams.
 from .api import (FuseError, Csr, fuse_cell, fuse_magg, fuse_magg_noalloc, fuse_row, fuse_outer,  # noqa: F401
                   fuse_cell_csr, fuse_magg_csr, check_csr, prepare_cell_csr, prepare_magg_csr,
                   prepare_cell, prepare_magg, prepare_row, prepare_outer,
-                  cache_stats, cache_clear, cache_disk_hits, last_source, last_kernel, probe_copy, probe_read,
+                  cache_stats, cache_clear, cache_disk_hits, last_source, last_kernel, probe_copy, probe_read, probe_gather,
                   AGG, SIDE, OPS, lib_path)

@@ -85,5 +85,7 @@ def load():
     lib.fuse_probe_copy.restype = ci
     lib.fuse_probe_read.argtypes = [vp, ctypes.c_int64, ci, vp, vp]
     lib.fuse_probe_read.restype = ci
+    lib.fuse_probe_gather.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, vp, ctypes.c_int64, ci, vp, vp]
+    lib.fuse_probe_gather.restype = ci
     _lib = lib
     return lib

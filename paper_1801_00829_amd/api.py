@@ -430,3 +430,16 @@ def probe_copy(dst, src, blocks, stream=None):
 
 def probe_read(src, sink, blocks, stream=None):
     _check(L.load().fuse_probe_read(src.data_ptr(), src.numel(), int(blocks), sink.data_ptr(), _stream(stream)))
+
+
+def probe_gather(table, idx, sink, blocks, stream=None):
+    """C: fuse_probe_gather.  table: cuda float64 (rows, row_doubles); idx: cuda int32 row numbers."""
+    import torch
+    if table.dtype != torch.float64 or idx.dtype != torch.int32 or table.dim() != 2 or table.stride(1) != 1:
+        raise TypeError("probe_gather needs a float64 table with unit column stride and int32 indices")
+    for t_, what in ((table, "table"), (idx, "idx"), (sink, "sink")):
+        _on_gpu(t_, what)
+    if not idx.is_contiguous():
+        raise ValueError("idx must be contiguous")
+    _check(L.load().fuse_probe_gather(table.data_ptr(), table.shape[0], table.shape[1], table.stride(0),
+                                      idx.data_ptr(), idx.numel(), int(blocks), sink.data_ptr(), _stream(stream)))

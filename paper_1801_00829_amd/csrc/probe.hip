@@ -46,7 +46,66 @@ __global__ void __launch_bounds__(256) probe_read_kernel(const double2_t *__rest
         sink[0] = acc;
 }
 
+// Gather of whole table rows at random: a group of 8 consecutive lanes reads row idx[k] of the table
+// (EPL 16-byte vectors per lane, vector e * 8 + lane, so that a load instruction of the group covers 128
+// contiguous bytes) for 4 values of k at a time, all loads issued before any is used -- the access pattern
+// of the Outer template's V_j fetch without any of its arithmetic, i.e. the rate at which this device
+// serves such gathers from a table of the given size (L2, memory-side cache or HBM resident).
+template <int EPL>
+__global__ void __launch_bounds__(256) probe_gather_kernel(const double2_t *__restrict__ table, long long ldv, int nvec,
+                                                           const int *__restrict__ idx, long long count,
+                                                           double *__restrict__ sink)
+{
+    constexpr int G = 8, UNR = 4;
+    const int lig = threadIdx.x & (G - 1);
+    const long long ngroups = (long long)gridDim.x * (256 / G);
+    long long k = (long long)blockIdx.x * (256 / G) + threadIdx.x / G;
+    double acc = 0.0;
+    for (; k < count; k += ngroups * UNR) {
+        double2_t v[UNR][EPL];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const long long kk = k + u * ngroups;
+            const long long row = kk < count ? idx[kk] : idx[k];
+            const double2_t *p = table + row * ldv;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) {
+                const int c = e * G + lig;
+                v[u][e] = p[c < nvec ? c : nvec - 1];          // redirected, not predicated: every lane loads
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u)
+#pragma unroll
+            for (int e = 0; e < EPL; ++e)
+                acc += v[u][e].x + v[u][e].y;
+    }
+    if (acc == 123.456789)
+        sink[0] = acc;
+}
+
 }  // namespace
+
+extern "C" int fuse_probe_gather(const double *table, int64_t rows, int64_t row_doubles, int64_t ld,
+                                 const int32_t *idx, int64_t count, int blocks, double *sink, void *stream)
+{
+    if (!table || !idx || !sink || rows < 1 || row_doubles < 2 || (row_doubles & 1) || row_doubles > 128 ||
+        ld < row_doubles || (ld & 1) || count < 0 || blocks < 1 || ((uintptr_t)table & 15u))
+        return FUSE_EINVAL;
+    if (count == 0)
+        return FUSE_OK;
+    const int nvec = (int)(row_doubles / 2), epl = (nvec + 7) / 8;
+    const double2_t *t = (const double2_t *)table;
+    hipStream_t s = (hipStream_t)stream;
+#define FUSE_GATHER_CASE(E) case E: probe_gather_kernel<E><<<blocks, 256, 0, s>>>(t, ld / 2, nvec, idx, count, sink); break;
+    switch (epl) {
+        FUSE_GATHER_CASE(1) FUSE_GATHER_CASE(2) FUSE_GATHER_CASE(3) FUSE_GATHER_CASE(4)
+        FUSE_GATHER_CASE(5) FUSE_GATHER_CASE(6) FUSE_GATHER_CASE(7) FUSE_GATHER_CASE(8)
+    default: return FUSE_EINVAL;
+    }
+#undef FUSE_GATHER_CASE
+    return hipGetLastError() == hipSuccess ? FUSE_OK : FUSE_ERUNTIME;
+}
 
 extern "C" int fuse_probe_copy(double *dst, const double *src, int64_t n_doubles, int blocks, void *stream)
 {
