@@ -1242,15 +1242,72 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         while (G % UNR)
             --UNR;
     }
+    // U-stationary form (FUSE_OUTER_STATIONARY, default 1): one block of 8 waves per CU keeps its rows of U in LDS and
+    // walks many small panels (FUSE_OUTER_SPANEL_KB of V each, default 4096) with them; taken when at least 64 rows of U
+    // fit into the LDS of a CU beside the books.  Rows per block and round: what balances the rounds, at most 256.
+    int stat_rcw = 0;                    // rows per block and round (0: another form)
+    const int SBLOCK = 512;
+    if (panels && env_int("FUSE_OUTER_STATIONARY", 1) != 0) {
+        const int64_t up = nvec * VEC;
+        const int64_t books = 3 * 256 * (4 + (X->rowptr_is64 ? 8 : 4)) + 3 * 4 * 4 + (SBLOCK / 64) * 8 + 32;   // all LDS beside the rows
+        const int64_t cap = std::min<int64_t>(256, ((int64_t)160 * 1024 - books) / (up * 8));
+        const int64_t blocks = rt.num_cus();
+        if (cap >= 64) {
+            const int64_t rounds = std::max<int64_t>(1, (X->rows + blocks * cap - 1) / (blocks * cap));
+            int64_t rb = (X->rows + rounds * blocks - 1) / (rounds * blocks);
+            if (env_int("FUSE_OUTER_RB", 0) > 0)
+                rb = env_int("FUSE_OUTER_RB", 0);
+            stat_rcw = (int)std::max<int64_t>(1, std::min<int64_t>(rb, cap));
+            // many small panels: U costs nothing per panel here
+            const int64_t vbytes = X->cols * V->ld * 8;
+            const int64_t pbytes = (int64_t)std::max(1, env_int("FUSE_OUTER_SPANEL_KB", 4096)) * 1024;
+            int64_t P = std::max<int64_t>(2, std::min<int64_t>(1024, (vbytes + pbytes - 1) / pbytes));
+            if (panel_mode == 2)
+                P = std::max<int64_t>(P, std::min<int64_t>(npanels, 1024));        // tests: tiny panels stay tiny
+            const int64_t W = std::max<int64_t>(1, (X->cols + P - 1) / P);
+            P = (X->cols + W - 1) / W;
+            if (P >= 2 && (P + 1) * X->rows * (X->rowptr_is64 ? 8 : 4) <= ((int64_t)1 << 30)) {
+                npanels = (int)P;
+                panel_w = (int)W;
+            } else {
+                stat_rcw = 0;
+            }
+        }
+    }
+    // Flat form of the panel walk (FUSE_OUTER_FLAT, default 1): a wave takes RC rows at a time and deals their
+    // cells inside the panel to its lane groups as one list; the chunk's U rows are staged in LDS.  RC: about 50
+    // cells per chunk and panel (a round of the wave holds 64), a power of two <= 16; the staged rows of a block
+    // (waves x RC x rank doubles) must fit in 60 KB.
+    int flat_rc = 0;
+    if (panels && !stat_rcw && env_int("FUSE_OUTER_FLAT", 1) != 0) {
+        const double per_row_panel = (double)X->nnz / (double)X->rows / (double)npanels;
+        int rc = env_int("FUSE_OUTER_RC", 0);
+        if (rc <= 0) {
+            rc = 1;
+            while (rc < 16 && per_row_panel * (rc * 2) <= 56.0)
+                rc <<= 1;
+        }
+        rc = std::min(16, next_pow2(rc));
+        const int64_t up = nvec * VEC;                       // LDS pitch of a staged row of U
+        while (rc > 1 && (int64_t)(BLOCK / 64) * rc * up * 8 > 60 * 1024)
+            rc >>= 1;
+        if ((int64_t)(BLOCK / 64) * rc * up * 8 <= 60 * 1024)
+            flat_rc = rc;
+    }
 
     // left_mm: by default over the transposed pattern of X (built per call in the workspace) as the right_mm
     // traversal with U and V exchanged; FUSE_OUTER_LEFT_TRANSPOSE=0 keeps the scatter with fp64 atomics
     const bool transposed = mode == 3 && env_int("FUSE_OUTER_LEFT_TRANSPOSE", 1) != 0 && X->rows <= 2147483647LL / 16;
     const int kmode = transposed ? 2 : mode;
     const bool out_vec = vec2 && (!launch || aligned16(out));
-    const std::string key = std::string("outer|") + (panels ? "panels|" : "") + prog.key + "|" + side_key(sides, nsides) + "|agg" +
+    const int flat_wpe = std::max(1, std::min(8, env_int("FUSE_OUTER_WPE", 3)));      // waves per SIMD the flat form is built for
+    const int KBLOCK = stat_rcw ? SBLOCK : BLOCK;                // threads per block of the main kernel
+    int sunr = env_int("FUSE_OUTER_SUNR", 2);                     // steps of a wave whose gathers leave together (stationary form)
+    sunr = (sunr >= 2 && G % 2 == 0) ? 2 : 1;
+    const std::string key = std::string("outer|") + (panels ? (stat_rcw ? "stat" + std::to_string(stat_rcw) + "r" + std::to_string(r) + "u" + std::to_string(sunr) + "|"
+                                                             : flat_rc ? "flat" + std::to_string(flat_rc) + "r" + std::to_string(r) + "w" + std::to_string(flat_wpe) + "|" : std::string("panels|")) : std::string("")) + prog.key + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(kmode) + (transposed ? "T" : "") + (kmode == 2 && out_vec ? "o" : "") + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
-                            std::to_string(EPL) + "u" + std::to_string(UNR) + "b" + std::to_string(BLOCK) + "w" +
+                            std::to_string(EPL) + "u" + std::to_string(UNR) + "b" + std::to_string(KBLOCK) + "w" +
                             std::to_string(X->rowptr_is64 != 0);
     std::shared_ptr<Plan> plan;
     rc = rt.plan(key, "fuse_outer", [&](const std::string &name) {
@@ -1260,9 +1317,12 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
         s += "#define FUSE_G " + std::to_string(G) + "\n#define FUSE_EPL " + std::to_string(EPL) +
              "\n#define FUSE_VEC " + std::to_string(VEC) + "\n#define FUSE_UNR " + std::to_string(UNR) +
-             "\n#define FUSE_BLOCK " + std::to_string(BLOCK) + "\n#define FUSE_MODE " +
+             "\n#define FUSE_BLOCK " + std::to_string(KBLOCK) + "\n#define FUSE_MODE " +
              std::to_string(kmode) + "\n#define FUSE_TRANSPOSED " + std::to_string(transposed) + "\n#define FUSE_OUT_VEC " + std::to_string(out_vec) + "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) +
-             "\n#define FUSE_NEED_COL " + std::to_string(need_col) + "\n#define FUSE_PANELS " + std::to_string(panels) + "\n";
+             "\n#define FUSE_NEED_COL " + std::to_string(need_col) + "\n#define FUSE_PANELS " + std::to_string(panels ? (stat_rcw ? 3 : flat_rc ? 2 : 1) : 0) +
+             "\n#define FUSE_RANK " + std::to_string(r) + "\n#define FUSE_RC " + std::to_string(std::max(flat_rc, 1)) +
+             "\n#define FUSE_RB " + std::to_string(std::max(stat_rcw, 1)) + "\n#define FUSE_SUNR " + std::to_string(sunr) +
+             "\n#define FUSE_WPE " + std::to_string(stat_rcw ? 2 : flat_wpe) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_outer_body(prog);
         s += kSrcOuter;
@@ -1292,7 +1352,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         // step with their XCD and evict the panel the others are using
         int bpc = env_int("FUSE_OUTER_PANEL_BLOCKS_PER_CU", 0);
         if (bpc <= 0)
-            bpc = rt.resident_blocks_per_cu(fn.main, BLOCK);
+            bpc = stat_rcw ? 1 : rt.resident_blocks_per_cu(fn.main, KBLOCK);
         gx = std::max<int64_t>(8, (int64_t)cus * bpc / 8 * 8);
         pp_doubles = (size_t)(npanels + 1) * (size_t)X->rows * (X->rowptr_is64 ? 8 : 4) / 8 + 1;
     }
@@ -1353,7 +1413,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         if ((rc = rt.launch(fn.prep, (unsigned)gp, 1, 256, stream, &A, sizeof A, g_err)))
             return rc;
     }
-    return rt.launch(fn.main, (unsigned)gx, 1, BLOCK, stream, &A, sizeof A, g_err);
+    return rt.launch(fn.main, (unsigned)gx, 1, KBLOCK, stream, &A, sizeof A, g_err);
 }
 
 int check_csr_device(const fuse_csr *X, void *stream_)

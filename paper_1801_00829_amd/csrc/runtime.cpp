@@ -191,7 +191,8 @@ int Runtime::load(Plan &p, Plan::Loaded &fn, std::string &err)
     if (e == hipSuccess)
         e = hipModuleGetFunction(&l.fill, l.module, "fuse_fill");
     if (e == hipSuccess && p.source.find("void __launch_bounds__(256) fuse_outer_prep") != std::string::npos &&
-        p.source.find("#define FUSE_PANELS 1") != std::string::npos)
+        (p.source.find("#define FUSE_PANELS 1") != std::string::npos || p.source.find("#define FUSE_PANELS 2") != std::string::npos ||
+         p.source.find("#define FUSE_PANELS 3") != std::string::npos))
         e = hipModuleGetFunction(&l.prep, l.module, "fuse_outer_prep");
     if (e != hipSuccess) {
         err = std::string("hipModuleGetFunction: ") + hipGetErrorString(e);

@@ -545,16 +545,24 @@ def test_row_csr_rejects_programs_that_are_not_sparse_safe():
 
 # ------------------------------------------------------------------------ Outer ---
 
-@pytest.fixture(params=["rows", "panels"])
+@pytest.fixture(params=["rows", "panels", "flat", "stationary"])
 def outer_mapping(request, monkeypatch):
-    """Both mappings of the no_agg / full_agg Outer skeleton: a wave per row, or column panels of V
-    (forced here with tiny panels; by default only chosen when V overflows an L2)."""
-    if request.param == "panels":
+    """The mappings of the no_agg / full_agg Outer skeleton: a wave per row, or column panels of V
+    (forced here with tiny panels; by default only chosen when V overflows an L2) with a lane group
+    per row ("panels"), with the cells of a chunk of rows dealt to the groups as one list ("flat"), or
+    with the rows of U stationary in LDS while the waves walk all panels ("stationary", the default
+    when the rank allows it)."""
+    if request.param == "rows":
+        monkeypatch.setenv("FUSE_OUTER_PANELS", "0")
+    else:
         monkeypatch.setenv("FUSE_OUTER_PANELS", "2")
         monkeypatch.setenv("FUSE_OUTER_PANEL_KB", "1")
-    else:
-        monkeypatch.setenv("FUSE_OUTER_PANELS", "0")
+        monkeypatch.setenv("FUSE_OUTER_STATIONARY", "1" if request.param == "stationary" else "0")
+        monkeypatch.setenv("FUSE_OUTER_FLAT", "1" if request.param == "flat" else "0")
     return request.param
+
+
+OUTER_FORM = {"rows": 0, "panels": 1, "flat": 2, "stationary": 3}
 
 
 @pytest.mark.parametrize("case", range(12 * MORE))
@@ -598,9 +606,14 @@ def test_outer_closed_forms_patterns_and_index_exactness(outer_mapping):
             rows = np.repeat(np.arange(m), np.diff(rp))
             assert np.array_equal(got, (rows + 1.0) * (ci + 1.0))
             # number of processed stored cells == rowptr[m]
+            host(xd.vals)                         # (synchronises) the source of the next call is inspected:
+            F.cache_clear()                       # make sure that it is compiled now, not found in the cache
             assert host(F.fuse_outer([("main",), ("neq0",)], xd, to_dev(u2), to_dev(v2), [], "full"))[0] == float(rp[-1])
             if n > 1 and va.size:
-                assert ("#define FUSE_PANELS 1" in F.last_source()) == (outer_mapping == "panels")
+                form = OUTER_FORM[outer_mapping]
+                if form == 3 and r > 2000:                     # too few rows of U fit into LDS: the flat form
+                    form = 2
+                assert "#define FUSE_PANELS %d\n" % form in F.last_source(), outer_mapping
     # zero rows of U: every stored cell of those rows contributes x * log(1e-15)
     rp, ci, va = W.csr_bernoulli(60, 50, 0.2, 11)
     u = np.ones((60, 100))
