@@ -287,6 +287,13 @@ int fuse_prepare_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr
 int fuse_prepare_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U,
                        const fuse_dense *V, const fuse_side *sides, int nsides, int agg);
 
+/* Number of fp64 values that `out` of the fuse_row call with the same arguments must hold (Table 1, row
+ * "Row": the shape of the result follows from the kind of the body's result -- row vector, per-row scalar,
+ * k-vector, row (x) k-vector -- and the variant).  Validates like fuse_prepare_row (data pointers may be
+ * NULL), compiles and launches nothing; same errors.  *count is written only on FUSE_OK. */
+int fuse_row_out_count(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
+                       const fuse_side *sides, int nsides, int agg, int64_t *count);
+
 /* Structure check of a CSR matrix, on the device (the template calls themselves trust the
  * format they are given: offsets or column indices that point outside the arrays make them
  * read outside the arrays).  Verifies rowptr[0] == 0, rowptr[rows] == nnz, non-decreasing

@@ -67,6 +67,8 @@ def load():
     lib.fuse_prepare_magg.argtypes = [P(Expr), ci, P(Dense), P(Side), ci]
     lib.fuse_prepare_row.argtypes = [P(Expr), P(Dense), P(CsrDesc), P(Side), ci, ci]
     lib.fuse_prepare_outer.argtypes = [P(Expr), P(CsrDesc), P(Dense), P(Dense), P(Side), ci, ci]
+    lib.fuse_row_out_count.argtypes = [P(Expr), P(Dense), P(CsrDesc), P(Side), ci, ci, i64p]
+    lib.fuse_row_out_count.restype = ci
     lib.fuse_check_csr.argtypes = [P(CsrDesc), vp]
     for f in (lib.fuse_check_csr, lib.fuse_cell_csr, lib.fuse_magg_csr, lib.fuse_prepare_cell_csr, lib.fuse_prepare_magg_csr,
               lib.fuse_cell, lib.fuse_magg, lib.fuse_magg_noalloc, lib.fuse_row, lib.fuse_outer, lib.fuse_prepare_cell,

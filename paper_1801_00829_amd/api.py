@@ -261,49 +261,12 @@ def prepare_magg_csr(exprs, shape, nnz, sides=(), rowptr64=False):
     _check(lib.fuse_prepare_magg_csr(ea, len(pairs), ctypes.byref(xs), sa, ns))
 
 
-def _row_result_kind(expr, sides):
-    """Kind of a Row body's result and k (only used to size the output): "S", "V", "K" or "VK"."""
-    st, kdim = [], 1
-    for t in expr:
-        name = t[0]
-        if name == "main":
-            st.append("V")
-        elif name == "side":
-            kind, val = sides[t[1]]
-            if kind in ("rhs", "kvec"):
-                kdim = int(val[1]) if isinstance(val, tuple) else int(val.shape[1])
-            st.append({"matrix": "V", "rowvec": "V", "rhs": "M", "kvec": "K"}.get(kind, "S"))
-        elif name == "const":
-            st.append("S")
-        elif name == "rowsum":
-            st.pop()
-            st.append("S")
-        elif name == "dot":
-            st.pop()
-            st.pop()
-            st.append("S")
-        elif name == "matmult":
-            st.pop()
-            st.pop()
-            st.append("K")
-        elif name == "outerk":
-            st.pop()
-            st.pop()
-            st.append("VK")
-        elif OPS.get(name, 0) >= 32:
-            b = st.pop()
-            a = st.pop()
-            st.append("V" if "V" in (a, b) else "K" if "K" in (a, b) else "S")
-    return (st[-1] if st else "S"), kdim
-
-
-def _row_count(agg, m, n, expr, sides, nnz=None):
-    kind, k = _row_result_kind(expr, sides)
-    if kind == "VK":
-        return n * k
-    if kind == "K":
-        return {"none": m * k, "full": 1}.get(agg, k)
-    return _agg_count(agg, m, n, kind == "V", nnz=nnz)
+def _row_out_count(lib, e, xd, xs, sa, ns, agg):
+    """C: fuse_row_out_count -- the library says how many values the result has."""
+    cnt = ctypes.c_int64()
+    _check(lib.fuse_row_out_count(ctypes.byref(e), ctypes.byref(xd) if xd is not None else None,
+                                  ctypes.byref(xs) if xs is not None else None, sa, ns, AGG[agg], ctypes.byref(cnt)))
+    return cnt.value
 
 
 def fuse_row(expr, X, sides=(), agg="col_t", out=None, stream=None):
@@ -315,15 +278,13 @@ def fuse_row(expr, X, sides=(), agg="col_t", out=None, stream=None):
         xs = _csr(X)
         m, n = xs.rows, xs.cols
         sa, ns = _sides(sides, m, n)
-        cnt = _row_count(agg, m, n, expr, sides, nnz=xs.nnz)
-        out = _out(out, cnt, X.vals)
+        out = _out(out, _row_out_count(lib, e, None, xs, sa, ns, agg), X.vals)
         _check(lib.fuse_row(ctypes.byref(e), None, ctypes.byref(xs), sa, ns, AGG[agg], out.data_ptr(),
                             _stream(stream)))
     else:
         xd = _dense(X)
         sa, ns = _sides(sides, xd.rows, xd.cols)
-        cnt = _row_count(agg, xd.rows, xd.cols, expr, sides)
-        out = _out(out, cnt, X)
+        out = _out(out, _row_out_count(lib, e, xd, None, sa, ns, agg), X)
         _check(lib.fuse_row(ctypes.byref(e), ctypes.byref(xd), None, sa, ns, AGG[agg], out.data_ptr(),
                             _stream(stream)))
     return out

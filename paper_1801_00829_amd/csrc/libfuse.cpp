@@ -1089,7 +1089,7 @@ int cell_csr_impl(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
 }
 
 int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, const fuse_side *sides,
-             int nsides, int agg, double *out, void *stream_, bool launch)
+             int nsides, int agg, double *out, void *stream_, bool launch, int64_t *count_only = nullptr)
 {
     g_err.clear();
     hipStream_t stream = (hipStream_t)stream_;
@@ -1121,6 +1121,17 @@ int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, co
             count = ac == 0 ? m * prog.kdim : ac == 3 ? prog.kdim : 1;
         else if (prog.result_kind == KIND_VK)
             count = n * prog.kdim;
+        if (count_only) {               // fuse_row_out_count: the variant must still be one the body has
+            const int rk = prog.result_kind;
+            if (rk == KIND_S && (ac == 2 || ac == 3))
+                return fail(FUSE_EDESC, "row / column aggregation needs a row-vector result");
+            if (rk == KIND_K && ac == 2)
+                return fail(FUSE_EDESC, "a k-vector result has the variants no_agg, col_agg and full_agg");
+            if (rk == KIND_VK && ac != 3)
+                return fail(FUSE_EDESC, "an OUTERK result needs FUSE_AGG_COL / FUSE_AGG_COL_T");
+            *count_only = count;
+            return 0;
+        }
         if (launch && !out && count > 0)
             return fail(FUSE_EINVAL, "out is NULL");
     }
@@ -1535,6 +1546,14 @@ int fuse_prepare_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr
                      int nsides, int agg)
 {
     return guarded([&] { return row_impl(expr, Xd, Xs, sides, nsides, agg, nullptr, nullptr, false); });
+}
+
+int fuse_row_out_count(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, const fuse_side *sides,
+                       int nsides, int agg, int64_t *count)
+{
+    if (!count)
+        return guarded([&] { g_err.clear(); return fail(FUSE_EINVAL, "count is NULL"); });
+    return guarded([&] { return row_impl(expr, Xd, Xs, sides, nsides, agg, nullptr, nullptr, false, count); });
 }
 
 int fuse_prepare_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,

@@ -258,8 +258,7 @@ def test_row_dense_random_expressions(case):
         got = host(F.fuse_row(expr, xd, sd, agg))
         ref = unfused.row_dense(expr, x, sides, agg)
         scale = _abs_scale(none_ref, agg, m, n if want == "V" else 1)
-        # per-row reductions feed later element-wise maths: allow for their conditioning
-        assert_close(got, ref, scale=scale, tol=1e-9, what="row dense %s" % agg)
+        assert_close(got, ref, scale=scale, tol=1e-10, what="row dense %s" % agg)
 
 
 @pytest.mark.parametrize("shape", [(7, 2050), (33, 3000), (12, 4097), (5, 9000), (3, 20000), (2, 32768)])
@@ -282,7 +281,7 @@ def test_row_dense_wide_rows_with_reductions(shape):
             ref = unfused.row_dense(expr, x, sides, agg)
             scale = _abs_scale(none_ref, agg.replace("col_t", "col"), m, n) if want == "V" else \
                 (None if agg == "none" else max(np.abs(none_ref).sum(), 1e-300))
-            assert_close(got.reshape(ref.shape), ref, scale=scale, tol=1e-9, what="row wide %s %s" % (want, agg))
+            assert_close(got.reshape(ref.shape), ref, scale=scale, tol=1e-10, what="row wide %s %s" % (want, agg))
     src = F.last_source()
     assert int(src[src.index("#define FUSE_WPR ") + 17:].split()[0]) > 1          # the generator's own definition
 
@@ -333,12 +332,12 @@ def test_row_dense_narrow_rows(shape, form, monkeypatch):
         got = host(F.fuse_row(expr, xd, sd, agg))
         ref = unfused.row_dense(expr, x, sides, agg)
         assert_close(got.reshape(ref.shape), ref, scale=_abs_scale(none_ref, agg.replace("col_t", "col"), m, n),
-                     tol=1e-9, what="row narrow %s" % agg)
+                     tol=1e-10, what="row narrow %s" % agg)
         assert ("#define FUSE_LDSX 1" in F.last_source()) == (form == "staged")
     # per-row scalar results
     expr_s = [("main",), ("side", 2), ("dot",), ("side", 1), ("add",)]
     got = host(F.fuse_row(expr_s, xd, sd, "none"))
-    assert_close(got.reshape(-1), unfused.row_dense(expr_s, x, sides, "none").reshape(-1), tol=1e-9, what="row narrow scalar")
+    assert_close(got.reshape(-1), unfused.row_dense(expr_s, x, sides, "none").reshape(-1), tol=1e-10, what="row narrow scalar")
 
 
 def test_row_dense_narrow_rows_with_a_row_stride_are_loaded_directly():
@@ -510,7 +509,7 @@ def test_row_csr_random_sparse_safe_expressions(case, csr_mapping):
             scale = np.abs(np.nan_to_num(none_ref, nan=0.0, posinf=0.0, neginf=0.0)).sum()
         else:
             scale = None
-        assert_close(got, ref, scale=None if scale is None else max(scale, 1e-300), tol=1e-9,
+        assert_close(got, ref, scale=None if scale is None else max(scale, 1e-300), tol=1e-10,
                      what="row csr %s" % agg)
 
 
@@ -584,7 +583,7 @@ def test_outer_random_expressions(case, outer_mapping):
         got = host(F.fuse_outer(expr, xd, ud, vd, sd, agg))
         ref = unfused.outer(expr, x, u, v, sides, agg)
         scale = None if agg == "none" else max(np.abs(np.nan_to_num(none_ref, nan=0, posinf=0, neginf=0)).sum(), 1e-300)
-        assert_close(got, ref, scale=scale, tol=1e-9 if agg == "full" else 1e-10, what="outer %s" % agg)
+        assert_close(got, ref, scale=scale, tol=1e-10, what="outer %s" % agg)
 
 
 def test_outer_closed_forms_patterns_and_index_exactness(outer_mapping):
@@ -719,7 +718,7 @@ def test_outer_mm_random_expressions(case, left_mm_form):
         ref = unfused.outer(expr, x, u, v, sides, agg)
         scale = unfused.outer([("side", 0)], x, u, v, [("matrix", np.zeros((m, n)))], agg)   # shape only
         absref = ops.csr_matmul_dense(x, w_abs, np.abs(v)) if agg == "right_mm" else ops.csr_t_matmul_dense(x, w_abs, np.abs(u))
-        assert_close(got, ref, scale=max(absref.max(initial=0.0), 1e-300), tol=1e-9, what="outer mm %s" % agg)
+        assert_close(got, ref, scale=max(absref.max(initial=0.0), 1e-300), tol=1e-10, what="outer mm %s" % agg)
 
 
 def test_outer_right_mm_unaligned_output_and_odd_rank():
@@ -1056,7 +1055,7 @@ def test_row_body_with_the_most_reductions_and_stages():
         nested = [("main",)] + nested + [("div",) if i % 2 == 0 else ("mul",), ("rowsum",)]
     for agg in ("none", "full"):
         got = host(F.fuse_row(nested, to_dev(x), [], agg))
-        assert_close(got, unfused.row_dense(nested, x, [], agg), tol=1e-9, what="five stages " + agg)
+        assert_close(got, unfused.row_dense(nested, x, [], agg), tol=1e-10, what="five stages " + agg)
     assert "#define FUSE_NSTAGE 5" in F.last_source()
 
 
