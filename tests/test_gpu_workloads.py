@@ -91,6 +91,51 @@ def test_outer_product_variants_full_size(agg):
     assert err.max() <= 1e-12, err.max()
 
 
+@pytest.mark.parametrize("sides_kind", ["matrix", "vectors"])
+def test_cell_variants_at_scale(sides_kind):
+    """All four variants of the Cell template (Table 1: no_agg, row_agg, col_agg, full_agg) on 100000 x 1000
+    (the size of the paper's Fig. 8 sweep where the inputs no longer fit any cache), every output element
+    against the oracle; with a matrix side input (flat form where it applies) and with column- and row-vector
+    side inputs (2-D form)."""
+    import paper_1801_00829_amd as F
+    m, n = 100_000, 1000
+    x = W.dense_uniform(m, n, -1.0, 1.0, 991)
+    if sides_kind == "matrix":
+        sides = [("matrix", W.dense_uniform(m, n, -1.0, 1.0, 992))]
+        expr = [("main",), ("side", 0), ("mul",)]
+    else:
+        sides = [("colvec", W.dense_uniform(m, 1, -1.0, 1.0, 993).reshape(m)),
+                 ("rowvec", W.dense_uniform(n, 1, -1.0, 1.0, 994).reshape(n))]
+        expr = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+    xd, sd = to_dev(x), dev_sides(sides)
+    none_ref = unfused.cell(expr, x, sides, "none").reshape(m, n)
+    absv = np.abs(none_ref)
+    for agg in ("none", "row", "col", "full"):
+        print("cell at scale:", sides_kind, agg, flush=True)
+        got = host(F.fuse_cell(expr, xd, sd, agg))
+        ref = none_ref if agg == "none" else unfused.cell(expr, x, sides, agg)
+        scale = None if agg == "none" else float(absv.sum()) if agg == "full" else \
+            float(absv.sum(1).max()) if agg == "row" else float(absv.sum(0).max())
+        assert_close(got, np.asarray(ref).reshape(-1), scale=scale, tol=TOL, what="cell %s %s" % (sides_kind, agg))
+
+
+def test_long_chain_expression_at_scale():
+    """The expression of the paper's instruction-footprint experiment (Sec. 5.3): sum(f(X / rowSums(X))) with f a
+    chain of 31 scalar operations, on 30000 x 1000 (the oracle materialises every one of the 33 intermediates);
+    the row aggregate feeds the chain, the chain the full aggregate."""
+    import paper_1801_00829_amd as F
+    m, n = 30_000, 1000
+    x = W.dense_uniform(m, n, 0.5, 1.5, 995)
+    expr = [("main",), ("main",), ("rowsum",), ("div",)]
+    for q in range(31):
+        expr += [("const", 1.0 + 1e-3 * (q + 1)), ("mul",)]
+    got = host(F.fuse_row(expr, to_dev(x), [], "full"))
+    ref = unfused.row_dense(expr, x, [], "full")
+    assert_close(got, ref, tol=TOL, what="long chain full")             # all summands positive
+    got = host(F.fuse_row(expr, to_dev(x), [], "row"))
+    assert_close(got, unfused.row_dense(expr, x, [], "row"), tol=TOL, what="long chain row")
+
+
 def test_calls_on_two_streams_keep_their_own_workspaces():
     """Every (device, stream) pair has its own block partials and arrival counter: operators that
     overlap on two streams (default priorities) must not disturb each other's aggregates."""
