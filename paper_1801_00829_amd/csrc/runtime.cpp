@@ -248,7 +248,9 @@ int Runtime::workspace(hipStream_t stream, size_t doubles, Workspace &ws, std::s
             return FUSE_ENOMEM;
         }
     }
-    if (w.partial_doubles < doubles) {
+    // (also for a request of 0 doubles on a stream without a workspace yet: callers use the buffer's
+    //  address, e.g. as the one dummy cell of a CSR matrix without stored cells, and it must never be null)
+    if (!w.partials || w.partial_doubles < doubles) {
         size_t want = doubles < 65536 ? 65536 : doubles + doubles / 4;
         double *np = nullptr;
         e = hipMalloc((void **)&np, want * sizeof(double));
