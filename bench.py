@@ -342,6 +342,10 @@ def sweep(args):
         report("tab1", "Outer X*log(U t(V)+1e-15) no_agg", [m, nc, r], timed(lambda: F.fuse_outer(LOGUV, xs, u, v, [], "none")), gather + 8 * nnz, nnz)
         report("tab1", "Outer ((X!=0)*(U t(V))) V right_mm", [m, nc, r], timed(lambda: F.fuse_outer(alscg, xs, u, v, [], "right_mm")), gather + 8 * r * m, nnz)
         report("tab1", "Outer t((X!=0)*(U t(V))) U left_mm", [m, nc, r], timed(lambda: F.fuse_outer(alscg, xs, u, v, [], "left_mm")), gather + 8 * r * nc, nnz)
+        pattern = F.outer_left_prepare(xs)
+        report("tab1", "Outer t((X!=0)*(U t(V))) U left_mm over a prepared pattern", [m, nc, r],
+               timed(lambda: F.fuse_outer_left(alscg, xs, pattern, u, v, [])), gather + 8 * r * nc, nnz)
+        del pattern
         del xs, u, v
 
 

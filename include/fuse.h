@@ -269,6 +269,29 @@ int fuse_row(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs,
 int fuse_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
                const fuse_side *sides, int nsides, int agg, double *out, void *stream);
 
+/* Outer LEFT_MM over a pattern prepared once (Sec. 2.2, first example: the ALS-CG update is evaluated in
+ * every iteration on the same X while U and V change).  fuse_outer LEFT_MM sorts X by column in every call;
+ * here that is done once:
+ *   fuse_outer_left_pattern_bytes : device bytes a prepared pattern of X takes (20 bytes per stored cell plus
+ *                                   the column offsets; 0 for a NULL / negative X);
+ *   fuse_outer_left_prepare       : writes the pattern of X -- its cells ordered by column: their rows, their
+ *                                   places in X's arrays and their values -- into `pattern` (device memory of that
+ *                                   many bytes, 16-byte aligned, owned by the caller); a few kernels on `stream`,
+ *                                   scratch from the library's per-stream workspace;
+ *   fuse_outer_left_values        : X has new values on the same structure: brings them into the pattern's order
+ *                                   again (one kernel; rowptr and colidx of X are not read);
+ *   fuse_outer_left               : fuse_outer LEFT_MM (same arguments, result and errors) over the pattern: MAIN is
+ *                                   the value the pattern holds since the last prepare / values call, X gives the
+ *                                   shape only.  The cells of a column are added in the pattern's order: calls with
+ *                                   one pattern are run-to-run deterministic.
+ * rows(X) < 2^27 (FUSE_EUNSUPPORTED beyond).  A pattern that was prepared for another structure than X's gives
+ * undefined results (but no access leaves the arrays of a pattern of the right size). */
+size_t fuse_outer_left_pattern_bytes(const fuse_csr *X);
+int fuse_outer_left_prepare(const fuse_csr *X, void *pattern, void *stream);
+int fuse_outer_left_values(const fuse_csr *X, void *pattern, void *stream);
+int fuse_outer_left(const fuse_expr *expr, const fuse_csr *X, const void *pattern, const fuse_dense *U,
+                    const fuse_dense *V, const fuse_side *sides, int nsides, double *out, void *stream);
+
 /* Validate a request and compile its body into the plan cache without
  * launching anything (no device needed: the target is FUSE_ARCH, default
  * gfx950, when no GPU is present).  Same arguments and errors as the calls

@@ -67,6 +67,14 @@ def load():
     lib.fuse_prepare_magg.argtypes = [P(Expr), ci, P(Dense), P(Side), ci]
     lib.fuse_prepare_row.argtypes = [P(Expr), P(Dense), P(CsrDesc), P(Side), ci, ci]
     lib.fuse_prepare_outer.argtypes = [P(Expr), P(CsrDesc), P(Dense), P(Dense), P(Side), ci, ci]
+    lib.fuse_outer_left_pattern_bytes.argtypes = [P(CsrDesc)]
+    lib.fuse_outer_left_pattern_bytes.restype = ctypes.c_size_t
+    lib.fuse_outer_left_prepare.argtypes = [P(CsrDesc), vp, vp]
+    lib.fuse_outer_left_prepare.restype = ci
+    lib.fuse_outer_left_values.argtypes = [P(CsrDesc), vp, vp]
+    lib.fuse_outer_left_values.restype = ci
+    lib.fuse_outer_left.argtypes = [P(Expr), P(CsrDesc), vp, P(Dense), P(Dense), P(Side), ci, vp, vp]
+    lib.fuse_outer_left.restype = ci
     lib.fuse_row_out_count.argtypes = [P(Expr), P(Dense), P(CsrDesc), P(Side), ci, ci, i64p]
     lib.fuse_row_out_count.restype = ci
     lib.fuse_check_csr.argtypes = [P(CsrDesc), vp]

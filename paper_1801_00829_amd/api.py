@@ -304,6 +304,40 @@ def fuse_outer(expr, X, U, V, sides=(), agg="full", out=None, stream=None):
     return out
 
 
+def outer_left_prepare(X, stream=None):
+    """C: fuse_outer_left_pattern_bytes + fuse_outer_left_prepare.  Returns the prepared pattern of X (a uint8
+    device tensor that the caller keeps for as long as it calls fuse_outer_left with it)."""
+    import torch
+    lib = L.load()
+    xs = _csr(X)
+    nbytes = int(lib.fuse_outer_left_pattern_bytes(ctypes.byref(xs)))
+    pattern = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=X.vals.device)
+    _check(lib.fuse_outer_left_prepare(ctypes.byref(xs), pattern.data_ptr(), _stream(stream)))
+    return pattern
+
+
+def outer_left_values(X, pattern, stream=None):
+    """C: fuse_outer_left_values.  X has new values on the same structure: refresh the pattern's copy."""
+    xs = _csr(X)
+    _on_gpu(pattern, "pattern")
+    _check(L.load().fuse_outer_left_values(ctypes.byref(xs), pattern.data_ptr(), _stream(stream)))
+
+
+def fuse_outer_left(expr, X, pattern, U, V, sides=(), out=None, stream=None):
+    """C: fuse_outer_left.  left_mm over a pattern from outer_left_prepare (values as of the last prepare /
+    outer_left_values call)."""
+    lib = L.load()
+    e, keep = _expr(expr)
+    xs = _csr(X)
+    ud, vd = _dense(U), _dense(V)
+    sa, ns = _sides(list(sides), xs.rows, xs.cols)
+    out = _out(out, xs.cols * ud.cols, X.vals)
+    _on_gpu(pattern, "pattern")
+    _check(lib.fuse_outer_left(ctypes.byref(e), ctypes.byref(xs), pattern.data_ptr(), ctypes.byref(ud), ctypes.byref(vd),
+                               sa, ns, out.data_ptr(), _stream(stream)))
+    return out
+
+
 def check_csr(X, stream=None):
     """C: fuse_check_csr.  Raises FuseError (FUSE_ESHAPE) if the CSR structure is malformed; waits for the stream."""
     lib = L.load()

@@ -1142,8 +1142,29 @@ int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, co
 }
 
 // ----------------------------------------------------------------------- outer --
+// Layout of a prepared left_mm pattern (fuse_outer_left_prepare): column offsets of X (cols + 1, of the width of
+// X's row offsets), the row of every cell by column (int32), the place of every such cell in X's arrays (as fp64,
+// exact below 2^53), and the cells' values in that order; every part a whole number of 16-byte granules.
+// Sizes in doubles.
+struct LeftPattern {
+    size_t ptr, row, perm, val;
+    size_t bytes() const { return (ptr + row + perm + val) * 8; }
+};
+LeftPattern left_pattern_layout(const fuse_csr *X)
+{
+    auto dbl = [](size_t bytes) { return (bytes + 15) / 16 * 2; };
+    LeftPattern l;
+    l.ptr = dbl((size_t)(X->cols + 1) * (X->rowptr_is64 ? 8 : 4));
+    l.row = dbl((size_t)X->nnz * 4);
+    l.perm = dbl((size_t)X->nnz * 8);
+    l.val = l.perm;
+    return l;
+}
+
+// pattern: a prepared left_mm pattern of X (device), or nullptr
 int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, const fuse_dense *V,
-               const fuse_side *sides, int nsides, int agg, double *out, void *stream_, bool launch)
+               const fuse_side *sides, int nsides, int agg, double *out, void *stream_, bool launch,
+               const void *pattern = nullptr, bool with_pattern = false)
 {
     g_err.clear();
     Runtime &rt = Runtime::get();
@@ -1308,7 +1329,11 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
 
     // left_mm: by default over the transposed pattern of X (built per call in the workspace) as the right_mm
     // traversal with U and V exchanged; FUSE_OUTER_LEFT_TRANSPOSE=0 keeps the scatter with fp64 atomics
-    const bool transposed = mode == 3 && env_int("FUSE_OUTER_LEFT_TRANSPOSE", 1) != 0 && X->rows <= 2147483647LL / 16;
+    if (with_pattern && (mode != 3 || X->rows > 2147483647LL / 16))
+        return fail(FUSE_EUNSUPPORTED, "a prepared pattern serves left_mm of a matrix with fewer than 2^27 rows");
+    if (with_pattern && launch && !pattern && X->nnz > 0)
+        return fail(FUSE_EINVAL, "pattern is NULL");
+    const bool transposed = with_pattern || (mode == 3 && env_int("FUSE_OUTER_LEFT_TRANSPOSE", 1) != 0 && X->rows <= 2147483647LL / 16);
     const int kmode = transposed ? 2 : mode;
     const bool out_vec = vec2 && (!launch || aligned16(out));
     const int flat_wpe = std::max(1, std::min(8, env_int("FUSE_OUTER_WPE", 3)));      // waves per SIMD the flat form is built for
@@ -1375,7 +1400,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
                  t_ptr = dbl((size_t)(X->cols + 1) * rpb), t_row = dbl((size_t)X->nnz * 4),
                  t_val = (size_t)X->nnz;
     if (transposed)
-        pp_doubles = t_scratch + t_ptr + t_row + t_val;
+        pp_doubles = with_pattern ? 0 : t_scratch + t_ptr + t_row + t_val;
     Workspace ws;
     if ((rc = rt.workspace(stream, part_doubles + pp_doubles, ws, g_err)))
         return rc;
@@ -1396,7 +1421,20 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     A.partials = ws.partials;
     A.ticket = ws.ticket;
     fill_side_args(A, sides, nsides);
-    if (transposed) {
+    if (with_pattern) {
+        // the prepared pattern: nothing is sorted here
+        const LeftPattern lp = left_pattern_layout(X);
+        const double *base = static_cast<const double *>(pattern);
+        A.x = base + lp.ptr + lp.row + lp.perm;
+        A.rowptr = base;
+        A.colidx = reinterpret_cast<const int *>(base + lp.ptr);
+        A.m = X->cols;
+        A.n = X->rows;
+        A.u = V->data;
+        A.v = U->data;
+        A.ldu = V->ld;
+        A.ldv = U->ld;
+    } else if (transposed) {
         double *base = ws.partials + part_doubles;
         void *scratch = base, *tptr = base + t_scratch;
         int *trow = reinterpret_cast<int *>(base + t_scratch + t_ptr);
@@ -1425,6 +1463,44 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
             return rc;
     }
     return rt.launch(fn.main, (unsigned)gx, 1, KBLOCK, stream, &A, sizeof A, g_err);
+}
+
+// values_only: the pattern exists, only the values of X are brought into its order again
+int outer_left_prepare_impl(const fuse_csr *X, void *pattern, void *stream_, bool values_only)
+{
+    g_err.clear();
+    int rc = check_csr(X, true);
+    if (rc)
+        return rc;
+    if (X->rows > 2147483647LL / 16)
+        return fail(FUSE_EUNSUPPORTED, "a prepared pattern serves left_mm of a matrix with fewer than 2^27 rows");
+    if (X->rows == 0 || X->cols == 0 || X->nnz == 0)
+        return 0;                              // calls with such a matrix never look at the pattern
+    if (!pattern)
+        return fail(FUSE_EINVAL, "pattern is NULL");
+    if (reinterpret_cast<uintptr_t>(pattern) & 15u)
+        return fail(FUSE_EINVAL, "pattern must be 16-byte aligned");
+    hipStream_t stream = (hipStream_t)stream_;
+    const LeftPattern lp = left_pattern_layout(X);
+    if (values_only) {
+        double *b = static_cast<double *>(pattern);
+        if (gather_launch(b + lp.ptr + lp.row + lp.perm, X->vals, b + lp.ptr + lp.row, X->nnz, stream))
+            return fail(FUSE_ERUNTIME, "fuse_outer_left_values: launch failed");
+        return 0;
+    }
+    const size_t scratch = (transpose_scratch_bytes(X->rows, X->cols, X->nnz, X->rowptr_is64) + 15) / 16 * 2;
+    Workspace ws;
+    if ((rc = Runtime::get().workspace(stream, 64 + scratch + (size_t)X->nnz, ws, g_err)))
+        return rc;
+    double *base = static_cast<double *>(pattern);
+    double *iota = ws.partials + 64 + scratch;
+    if (iota_launch(iota, X->nnz, stream) ||
+        transpose_launch(X->rowptr, X->rowptr_is64, X->colidx, iota, X->rows, X->cols, X->nnz, ws.partials + 64, base,
+                         reinterpret_cast<int *>(base + lp.ptr), base + lp.ptr + lp.row, stream))
+        return fail(FUSE_ERUNTIME, "fuse_outer_left_prepare: launching the pattern transposition failed");
+    if (gather_launch(base + lp.ptr + lp.row + lp.perm, X->vals, base + lp.ptr + lp.row, X->nnz, stream))
+        return fail(FUSE_ERUNTIME, "fuse_outer_left_prepare: launch failed");
+    return 0;
 }
 
 int check_csr_device(const fuse_csr *X, void *stream_)
@@ -1508,6 +1584,29 @@ int fuse_outer(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
                const fuse_side *sides, int nsides, int agg, double *out, void *stream)
 {
     return guarded([&] { return outer_impl(expr, X, U, V, sides, nsides, agg, out, stream, true); });
+}
+
+size_t fuse_outer_left_pattern_bytes(const fuse_csr *X)
+{
+    if (!X || X->rows < 0 || X->cols < 0 || X->nnz < 0)
+        return 0;
+    return left_pattern_layout(X).bytes();
+}
+
+int fuse_outer_left_prepare(const fuse_csr *X, void *pattern, void *stream)
+{
+    return guarded([&] { return outer_left_prepare_impl(X, pattern, stream, false); });
+}
+
+int fuse_outer_left_values(const fuse_csr *X, void *pattern, void *stream)
+{
+    return guarded([&] { return outer_left_prepare_impl(X, pattern, stream, true); });
+}
+
+int fuse_outer_left(const fuse_expr *expr, const fuse_csr *X, const void *pattern, const fuse_dense *U,
+                    const fuse_dense *V, const fuse_side *sides, int nsides, double *out, void *stream)
+{
+    return guarded([&] { return outer_impl(expr, X, U, V, sides, nsides, FUSE_AGG_LEFT_MM, out, stream, true, pattern, true); });
 }
 
 int fuse_cell_csr(const fuse_expr *expr, const fuse_csr *X, const fuse_side *sides, int nsides, int agg,

@@ -121,4 +121,7 @@ size_t transpose_scratch_bytes(long long m, long long n, long long nnz, int rowp
 int transpose_launch(const void *rowptr, int rowptr_is64, const int *colidx, const double *vals, long long m, long long n,
                      long long nnz, void *scratch, void *tptr, int *trow, double *tval, hipStream_t stream);
 
+int iota_launch(double *dst, long long n, hipStream_t stream);     // dst[i] = (double)i
+int gather_launch(double *dst, const double *src, const double *perm, long long n, hipStream_t stream);   // dst[i] = src[perm[i]]
+
 }  // namespace fuse

@@ -358,6 +358,47 @@ int transpose_typed(const void *rowptr, const int *colidx, const double *vals, l
 
 namespace fuse {
 
+namespace {
+__global__ void __launch_bounds__(256) iota_kernel(double *__restrict__ dst, long long n)
+{
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256)
+        dst[i] = (double)i;
+}
+}  // namespace
+
+// dst[i] = i as a double (exact below 2^53): "values" that make the transposition carry every cell's place in the
+// original arrays along, i.e. produce the permutation instead of permuted values
+int iota_launch(double *dst, long long n, hipStream_t stream)
+{
+    if (n <= 0)
+        return 0;
+    const long long blocks = (n + 255) / 256;
+    iota_kernel<<<(unsigned)(blocks < 4096 ? blocks : 4096), 256, 0, stream>>>(dst, n);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+namespace {
+__global__ void __launch_bounds__(256) gather_kernel(double *__restrict__ dst, const double *__restrict__ src,
+                                                     const double *__restrict__ perm, long long n)
+{
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        long long p = (long long)__builtin_nontemporal_load(&perm[i]);
+        p = p < 0 ? 0 : (p < n ? p : n - 1);               // (a foreign pattern cannot lead outside the array)
+        dst[i] = src[p];
+    }
+}
+}  // namespace
+
+// dst[i] = src[perm[i]] for a permutation stored as doubles: the values of a matrix in the order of a prepared pattern
+int gather_launch(double *dst, const double *src, const double *perm, long long n, hipStream_t stream)
+{
+    if (n <= 0)
+        return 0;
+    const long long blocks = (n + 255) / 256;
+    gather_kernel<<<(unsigned)(blocks < 8192 ? blocks : 8192), 256, 0, stream>>>(dst, src, perm, n);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 size_t transpose_scratch_bytes(long long m, long long n, long long nnz, int rowptr_is64)
 {
     const size_t rpb = rowptr_is64 ? 8 : 4;

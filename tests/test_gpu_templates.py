@@ -699,6 +699,41 @@ def test_outer_left_mm_on_all_patterns(rowptr64, left_mm_form):
     _outer_mm_on_all_patterns("left_mm", rowptr64, left_mm_form)
 
 
+@pytest.mark.parametrize("rowptr64", [False, True])
+def test_outer_left_mm_over_a_prepared_pattern(rowptr64):
+    """fuse_outer_left: the column-sorted pattern of X is prepared once and reused while U and V -- and, after a
+    fuse_outer_left_values call, the values of X -- change from call to call (the ALS-CG loop of Sec. 2.2 evaluates its update on the same X in every iteration);
+    every call against the oracle and against fuse_outer LEFT_MM, which sorts per call."""
+    import torch
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(4100 + rowptr64)
+    body = [("main",), ("uvdot",), ("mul",), ("side", 0), ("add",)]              # looks at the value and at a side input at (i, j)
+    for name, (rp, ci, va), shape in _csr_cases():
+        m, n = shape
+        r = 20
+        xd = dev_csr(rp, ci, va, shape, rowptr64)
+        pattern = F.outer_left_prepare(xd)
+        side = rng.uniform(size=(m, n))
+        sd = dev_sides([("matrix", side)])
+        for it in range(3):
+            print("prepared left_mm", name, shape, "call", it, flush=True)
+            vals = va * (1.0 + it) + 0.25 * it
+            u, v = rng.uniform(size=(m, r)), rng.uniform(size=(n, r))
+            xd.vals.copy_(torch.from_numpy(vals))                                    # same structure, new values
+            if it:
+                F.outer_left_values(xd, pattern)
+            ud, vd = to_dev(u), to_dev(v)
+            got = host(F.fuse_outer_left(body, xd, pattern, ud, vd, sd))
+            x = ops.make_csr(rp, ci, vals, shape)
+            ref = unfused.outer(body, x, u, v, [("matrix", side)], "left_mm")
+            w_abs = np.abs(unfused.outer(body, x, u, v, [("matrix", side)], "none"))
+            absref = ops.csr_t_matmul_dense(x, w_abs, np.abs(u))
+            assert_close(got, ref, scale=max(absref.max(initial=0.0), 1e-300), tol=1e-10, what="prepared left_mm " + name)
+            per_call = host(F.fuse_outer(body, xd, ud, vd, sd, "left_mm"))
+            assert_close(got, per_call, scale=max(absref.max(initial=0.0), 1e-300), tol=1e-12, what="prepared vs per call " + name)
+            assert np.array_equal(got, host(F.fuse_outer_left(body, xd, pattern, ud, vd, sd)))      # one pattern: one order of sums
+
+
 @pytest.mark.parametrize("case", range(8 * MORE))
 def test_outer_mm_random_expressions(case, left_mm_form):
     import paper_1801_00829_amd as F
