@@ -16,6 +16,7 @@ Prints ONE JSON line:
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--templates cell,magg,...] [--no-cpu-baseline]
     python bench.py --sweep [groups]     timing sweep over the paper's micro-benchmark sizes instead (see sweep())
+    python bench.py --cell-budget        where the time of the 24 MB Cell workload goes (see cell_budget())
 """
 import argparse
 import json
@@ -350,6 +351,70 @@ def sweep(args):
 
 
 
+def cell_budget(args):
+    """Where the time of the 24 MB Cell workload (sum(X*Y*Z), 1000 x 1000: 3 us at the HBM peak) goes.  Prints
+    one JSON line per measurement, median and minimum of HIP-event brackets (microseconds), inputs cold (512 MB
+    written between launches) unless stated: a kernel that reads nothing, a kernel with one 16-byte load (first-byte
+    latency), a plain read of 24 MB with several grids (fuse_probe_read: no arithmetic, no reduction), and the Cell
+    operator across its launch shapes (threads per block, loads in flight per thread, number of blocks).  Run under
+    `rocprofv3 --kernel-trace --stats` the same command gives the kernels' own durations without the bracket."""
+    import numpy as np
+    import torch
+    import paper_1801_00829_amd as F
+    import workloads as W
+    if not torch.cuda.is_available():
+        sys.exit("bench.py --cell-budget needs a GPU")
+    w = W.make_workload("cell", 1.0)
+    x = torch.from_numpy(w["X"]).cuda()
+    sd = [(k, torch.from_numpy(np.asarray(v)).cuda()) for k, v in w["sides"]]
+    out = torch.empty(1, dtype=torch.float64, device="cuda")
+    evict = torch.empty(1 << 26, dtype=torch.float64, device="cuda")
+    sink = torch.zeros(1, dtype=torch.float64, device="cuda")
+    buf = torch.rand(3_000_000, dtype=torch.float64, device="cuda")
+
+    def timed(fn, cold=True, iters=20):
+        fn()
+        ts = []
+        for _ in range(iters):
+            if cold:
+                evict.fill_(1.0)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn()
+            b.record()
+            ts.append((a, b))
+        torch.cuda.synchronize()
+        t = sorted(a.elapsed_time(b) * 1e3 for a, b in ts)
+        return round(t[len(t) // 2], 2), round(t[0], 2)
+
+    def report(what, fn, **kw):
+        med, mn = timed(fn, **kw)
+        print(json.dumps({"what": what, "median_us": med, "min_us": mn, "cold": kw.get("cold", True)}), flush=True)
+
+    report("kernel that reads nothing (1 block)", lambda: F.probe_read(buf, sink, 1, n_doubles=0))
+    report("kernel with one 16-byte load (1 block)", lambda: F.probe_read(buf, sink, 1, n_doubles=2))
+    for blocks in (256, 512, 1024, 2048):
+        report("plain read of 24 MB, %d blocks of 256 threads" % blocks, lambda: F.probe_read(buf, sink, blocks))
+    report("plain read of 24 MB, 2048 blocks, inputs cache-resident", lambda: F.probe_read(buf, sink, 2048), cold=False)
+    shapes = [{}, {"FUSE_CELL_BLOCK": 512}, {"FUSE_CELL_BLOCK": 1024}, {"FUSE_CELL_BLOCK": 1024, "FUSE_CELL_UNROLL": 2},
+              {"FUSE_CELL_BLOCK": 1024, "FUSE_CELL_UNROLL": 1}, {"FUSE_CELL_BLOCK": 512, "FUSE_CELL_UNROLL": 2},
+              {"FUSE_CELL_UNROLL": 2, "FUSE_CELL_BLOCKS_PER_CU": 4}, {"FUSE_CELL_GRID": 128}, {"FUSE_CELL_GRID": 256},
+              {"FUSE_CELL_UNROLL": 2, "FUSE_CELL_GRID": 1024}]
+    for env in shapes:
+        for k_, v_ in env.items():
+            os.environ[k_] = str(v_)
+        try:
+            call = lambda: F.fuse_cell(w["expr"], x, sd, "full", out=out)
+            call()
+            name = F.last_kernel()
+            report("fuse_cell %s (%s)" % (env or "default launch shape", name), call)
+            if not env:
+                report("fuse_cell default launch shape, inputs cache-resident (%s)" % name, call, cold=False)
+        finally:
+            for k_ in env:
+                os.environ.pop(k_, None)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -365,6 +430,8 @@ def main():
                          "(comma-separated groups, see sweep(); default all)")
     ap.add_argument("--max-rows", type=int, default=1_000_000, help="--sweep: largest number of rows of the Fig. 8 groups")
     ap.add_argument("--iters", type=int, default=7, help="--sweep: timed calls per point (median reported)")
+    ap.add_argument("--cell-budget", action="store_true",
+                    help="time budget of the 24 MB Cell workload instead of the benchmark line (see cell_budget())")
     ap.add_argument("--cpu-baseline-child", default=None, help=argparse.SUPPRESS)
     args = ap.parse_args()
     if args.cpu_baseline_child is not None:
@@ -380,6 +447,9 @@ def main():
 
     if args.sweep is not None:
         sweep(args)
+        return
+    if args.cell_budget:
+        cell_budget(args)
         return
 
     import numpy as np
@@ -546,16 +616,19 @@ def main():
 
         def gather_rate(rows, idx):
             table = torch.rand(rows, r, dtype=torch.float64, device="cuda")
-            ts = []
-            for k in range(7):
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                F.probe_gather(table, idx, sink, 1024)
-                b.record()
-                ts.append((a, b))
-            torch.cuda.synchronize()
-            t = sorted(a.elapsed_time(b) for a, b in ts[2:])[len(ts[2:]) // 2] * 1e-3
-            return idx.numel() / t
+            best = 0.0
+            for blocks in (768, 1024):                     # 3 and 4 resident blocks per CU: the better one counts
+                ts = []
+                for k in range(7):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    F.probe_gather(table, idx, sink, blocks)
+                    b.record()
+                    ts.append((a, b))
+                torch.cuda.synchronize()
+                t = sorted(a.elapsed_time(b) for a, b in ts[2:])[len(ts[2:]) // 2] * 1e-3
+                best = max(best, idx.numel() / t)
+            return best
 
         def rnd(rows):
             return torch.randint(0, rows, (cnt,), dtype=torch.int32, device="cuda")
@@ -564,7 +637,7 @@ def main():
         sizes = {"l2_resident_2MB": 2_000_000 // row_bytes, "cache_resident_80MB": 80_000_000 // row_bytes,
                  "hbm_resident_2GB": 2_000_000_000 // row_bytes}
         ceilings = {"what": "fuse_probe_gather: %d random rows of %d bytes, 8 lanes per row, 4 rows in flight per group, "
-                            "1024 blocks; median of 5" % (cnt, row_bytes), "rows_per_s": {}, "GBps": {}}
+                            "768 or 1024 blocks (the faster); median of 5" % (cnt, row_bytes), "rows_per_s": {}, "GBps": {}}
         for key, rows in sizes.items():
             rate = gather_rate(rows, rnd(rows))
             ceilings["rows_per_s"][key] = float("%.4g" % rate)

@@ -423,8 +423,12 @@ def probe_copy(dst, src, blocks, stream=None):
     _check(L.load().fuse_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel(), int(blocks), _stream(stream)))
 
 
-def probe_read(src, sink, blocks, stream=None):
-    _check(L.load().fuse_probe_read(src.data_ptr(), src.numel(), int(blocks), sink.data_ptr(), _stream(stream)))
+def probe_read(src, sink, blocks, stream=None, n_doubles=None):
+    """C: fuse_probe_read over the first n_doubles values of src (default all; 0: a kernel that reads nothing)."""
+    n = src.numel() if n_doubles is None else int(n_doubles)
+    if n < 0 or n > src.numel():
+        raise ValueError("n_doubles out of range")
+    _check(L.load().fuse_probe_read(src.data_ptr(), n, int(blocks), sink.data_ptr(), _stream(stream)))
 
 
 def probe_gather(table, idx, sink, blocks, stream=None):

@@ -786,10 +786,14 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
     int UNROLL = env_int("FUSE_CELL_UNROLL", 0);
     if (UNROLL <= 0)
         UNROLL = nmat <= 1 ? 8 : (nmat <= 4 ? 4 : 2);
+    // threads per block (FUSE_CELL_BLOCK: 256, 512 or 1024; 0 = by rule)
+    int CBLOCK = env_int("FUSE_CELL_BLOCK", 0);
+    if (CBLOCK != 256 && CBLOCK != 512 && CBLOCK != 1024)
+        CBLOCK = 256;
 
     const std::string key = std::string(is_magg ? "magg|" : "cell|") + prog.key + "|" +
                             side_key(sides, nsides) + "|agg" + std::to_string(ac) + "|v" + std::to_string(VEC) +
-                            "u" + std::to_string(UNROLL) + "nt" + std::to_string(env_int("FUSE_NT", 1));
+                            "u" + std::to_string(UNROLL) + "b" + std::to_string(CBLOCK) + "nt" + std::to_string(env_int("FUSE_NT", 1));
     std::shared_ptr<Plan> plan;
     const char *not_ready = "fuse_magg_noalloc: this operator is not compiled and loaded on the current device yet; "
                             "call fuse_magg once with the same descriptor, side kinds and pointer alignment first";
@@ -801,7 +805,8 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
         s += kSrcCommon;
         s += "#define FUSE_KERNEL_NAME " + name + "\n";
         s += "#define FUSE_K " + std::to_string(k) + "\n#define FUSE_VEC " + std::to_string(VEC) +
-             "\n#define FUSE_UNROLL " + std::to_string(UNROLL) + "\n#define FUSE_FULL " + std::to_string(ac == 1) + "\n";
+             "\n#define FUSE_UNROLL " + std::to_string(UNROLL) + "\n#define FUSE_BLOCK " + std::to_string(CBLOCK) +
+             "\n#define FUSE_FULL " + std::to_string(ac == 1) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += "#define FUSE_SIDE_IS_MATRIX(k) (fuse_side_kind[k] == 0 && fuse_side_used[k])\n";
         s += emit_cell_body(prog);
@@ -826,7 +831,7 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
         return zero_fill(fn, out, ac == 1 ? k : 0, stream);
     const int64_t nvec = N / VEC;
     const int cus = rt.num_cus();
-    int64_t gx = std::max<int64_t>(nvec / ((int64_t)256 * UNROLL), (N + 255) / 256 > 4 ? 4 : 1);
+    int64_t gx = std::max<int64_t>(nvec / ((int64_t)CBLOCK * UNROLL), (N + CBLOCK - 1) / CBLOCK > 4 ? 4 : 1);
     gx = std::max<int64_t>(1, std::min<int64_t>(gx, (int64_t)cus * env_int("FUSE_CELL_BLOCKS_PER_CU", 1)));
     // small inputs: the cost of finishing (one arrival ticket and one partial per block, summed by the last block)
     // grows with the number of blocks, so a block gets at least 128 KB to read (24 MB: 183 blocks, 11.4 us cold
@@ -855,7 +860,7 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
     A.partials = ws.partials;
     A.ticket = ws.ticket;
     fill_side_args(A, sides, nsides);
-    return rt.launch(fn.main, (unsigned)gx, 1, 256, stream, &A, sizeof A, g_err);
+    return rt.launch(fn.main, (unsigned)gx, 1, CBLOCK, stream, &A, sizeof A, g_err);
 }
 
 // ------------------------------------------------------------------------- row --
@@ -1278,7 +1283,9 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     // walks many small panels (FUSE_OUTER_SPANEL_KB of V each, default 4096) with them; taken when at least 64 rows of U
     // fit into the LDS of a CU beside the books.  Rows per block and round: what balances the rounds, at most 256.
     int stat_rcw = 0;                    // rows per block and round (0: another form)
-    const int SBLOCK = 512;
+    int SBLOCK = env_int("FUSE_OUTER_SBLOCK", 512);             // threads of the one block per CU: 8 waves (12 and 16 measured: slower)
+    if (SBLOCK != 512 && SBLOCK != 768 && SBLOCK != 1024)
+        SBLOCK = 512;
     if (panels && env_int("FUSE_OUTER_STATIONARY", 1) != 0) {
         const int64_t up = nvec * VEC;
         const int64_t books = 3 * 256 * (4 + (X->rowptr_is64 ? 8 : 4)) + 3 * 4 * 4 + (SBLOCK / 64) * 8 + 32;   // all LDS beside the rows
@@ -1358,7 +1365,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
              "\n#define FUSE_NEED_COL " + std::to_string(need_col) + "\n#define FUSE_PANELS " + std::to_string(panels ? (stat_rcw ? 3 : flat_rc ? 2 : 1) : 0) +
              "\n#define FUSE_RANK " + std::to_string(r) + "\n#define FUSE_RC " + std::to_string(std::max(flat_rc, 1)) +
              "\n#define FUSE_RB " + std::to_string(std::max(stat_rcw, 1)) + "\n#define FUSE_SUNR " + std::to_string(sunr) +
-             "\n#define FUSE_WPE " + std::to_string(stat_rcw ? 2 : flat_wpe) + "\n";
+             "\n#define FUSE_WPE " + std::to_string(stat_rcw ? SBLOCK / 256 : flat_wpe) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_outer_body(prog);
         s += kSrcOuter;

@@ -73,4 +73,12 @@ int noalloc_workspace(hipStream_t stream, Workspace &ws, std::string &err)
     return 0;
 }
 
+// ticket[0 .. 64) = 0 on `stream` (the arrival counter of a freshly allocated per-stream workspace: cleared by a
+// kernel on the caller's stream, like every other operation of a call, not by a host-synchronous memset)
+int reset_ticket_launch(unsigned int *ticket, hipStream_t stream)
+{
+    noalloc_reset_kernel<<<1, 64, 0, stream>>>(ticket);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 }  // namespace fuse

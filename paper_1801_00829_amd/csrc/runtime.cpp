@@ -240,9 +240,11 @@ int Runtime::workspace(hipStream_t stream, size_t doubles, Workspace &ws, std::s
     Workspace &w = ws_[std::make_pair(dev, stream)];
     if (!w.ticket) {
         e = hipMalloc((void **)&w.ticket, 256);
-        if (e == hipSuccess)
-            e = hipMemset(w.ticket, 0, 256);
+        if (e == hipSuccess && reset_ticket_launch(w.ticket, stream))     // cleared on the caller's stream, no host sync
+            e = hipErrorLaunchFailure;
         if (e != hipSuccess) {
+            if (w.ticket)
+                (void)hipFree(w.ticket);
             w.ticket = nullptr;
             err = std::string("workspace ticket: ") + hipGetErrorString(e);
             return FUSE_ENOMEM;

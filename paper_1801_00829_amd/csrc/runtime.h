@@ -108,6 +108,7 @@ private:
 // a file-scope device array, FUSE_NOALLOC_MAX_PARTIALS doubles of block partials behind a zeroed arrival
 // counter.  Enqueues one small kernel on `stream` that clears the counter.  0 on success.
 int noalloc_workspace(hipStream_t stream, Workspace &ws, std::string &err);
+int reset_ticket_launch(unsigned int *ticket, hipStream_t stream);      // 64 words at `ticket` = 0, by a kernel on `stream`
 
 // Launches the CSR structure check (check.hip); `bad` points to four device words, the first
 // three preset to all ones and the last to zero.  0 on success.
