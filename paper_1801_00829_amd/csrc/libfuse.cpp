@@ -1286,7 +1286,12 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     int SBLOCK = env_int("FUSE_OUTER_SBLOCK", 512);             // threads of the one block per CU: 8 waves (12 and 16 measured: slower)
     if (SBLOCK != 512 && SBLOCK != 768 && SBLOCK != 1024)
         SBLOCK = 512;
-    if (panels && env_int("FUSE_OUTER_STATIONARY", 1) != 0) {
+    // Only where re-reading U per panel is what costs: with many cells per row and panel the streamed-U form with a lane
+    // group per row (U_i in registers, 3 waves per SIMD) is the faster one -- 2e4 x 2e4, rank 100, a tenth of the cells
+    // stored: 23 against 19.6 Gcells/s; a hundredth: 18 against 17 (FUSE_OUTER_STATIONARY: 0 never, 1 by this rule, 2 always).
+    const int stat_mode = env_int("FUSE_OUTER_STATIONARY", 1);
+    const bool stat_pays = panels && (double)X->nnz / (double)X->rows / (double)npanels <= 16.0;
+    if (panels && stat_mode != 0 && (stat_mode == 2 || panel_mode == 2 || stat_pays)) {
         const int64_t up = nvec * VEC;
         const int64_t books = 3 * 256 * (4 + (X->rowptr_is64 ? 8 : 4)) + 3 * 4 * 4 + (SBLOCK / 64) * 8 + 32;   // all LDS beside the rows
         const int64_t cap = std::min<int64_t>(256, ((int64_t)160 * 1024 - books) / (up * 8));
@@ -1318,7 +1323,8 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     // cells per chunk and panel (a round of the wave holds 64), a power of two <= 16; the staged rows of a block
     // (waves x RC x rank doubles) must fit in 60 KB.
     int flat_rc = 0;
-    if (panels && !stat_rcw && env_int("FUSE_OUTER_FLAT", 1) != 0) {
+    if (panels && !stat_rcw && env_int("FUSE_OUTER_FLAT", 1) != 0 &&
+        (panel_mode == 2 || (double)X->nnz / (double)X->rows / (double)npanels <= 16.0)) {
         const double per_row_panel = (double)X->nnz / (double)X->rows / (double)npanels;
         int rc = env_int("FUSE_OUTER_RC", 0);
         if (rc <= 0) {
@@ -1343,7 +1349,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     const bool transposed = with_pattern || (mode == 3 && env_int("FUSE_OUTER_LEFT_TRANSPOSE", 1) != 0 && X->rows <= 2147483647LL / 16);
     const int kmode = transposed ? 2 : mode;
     const bool out_vec = vec2 && (!launch || aligned16(out));
-    const int flat_wpe = std::max(1, std::min(8, env_int("FUSE_OUTER_WPE", 3)));      // waves per SIMD the flat form is built for
+    const int flat_wpe = std::max(1, std::min(8, env_int("FUSE_OUTER_WPE", 2)));      // waves per SIMD the flat form is built for (3: spills, 898 against 810 us)
     const int KBLOCK = stat_rcw ? SBLOCK : BLOCK;                // threads per block of the main kernel
     int sunr = env_int("FUSE_OUTER_SUNR", 2);                     // steps of a wave whose gathers leave together (stationary form)
     sunr = (sunr >= 2 && G % 2 == 0) ? 2 : 1;
