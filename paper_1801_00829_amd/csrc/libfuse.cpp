@@ -1283,9 +1283,12 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     // walks many small panels (FUSE_OUTER_SPANEL_KB of V each, default 4096) with them; taken when at least 64 rows of U
     // fit into the LDS of a CU beside the books.  Rows per block and round: what balances the rounds, at most 256.
     int stat_rcw = 0;                    // rows per block and round (0: another form)
-    int SBLOCK = env_int("FUSE_OUTER_SBLOCK", 512);             // threads of the one block per CU: 8 waves (12 and 16 measured: slower)
+    // threads of the one block per CU: 12 waves with one step of gathers in flight each (133 registers) -- config 5: 8 waves
+    // with two steps 615 - 630 us, 12 waves with one 560 - 570, 16 waves with one (128 registers, no spills) 680; two steps
+    // at 12 waves spill (680 us and more)
+    int SBLOCK = env_int("FUSE_OUTER_SBLOCK", 768);
     if (SBLOCK != 512 && SBLOCK != 768 && SBLOCK != 1024)
-        SBLOCK = 512;
+        SBLOCK = 768;
     // Only where re-reading U per panel is what costs: with many cells per row and panel the streamed-U form with a lane
     // group per row (U_i in registers, 3 waves per SIMD) is the faster one -- 2e4 x 2e4, rank 100, a tenth of the cells
     // stored: 23 against 19.6 Gcells/s; a hundredth: 18 against 17 (FUSE_OUTER_STATIONARY: 0 never, 1 by this rule, 2 always).
@@ -1351,7 +1354,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     const bool out_vec = vec2 && (!launch || aligned16(out));
     const int flat_wpe = std::max(1, std::min(8, env_int("FUSE_OUTER_WPE", 2)));      // waves per SIMD the flat form is built for (3: spills, 898 against 810 us)
     const int KBLOCK = stat_rcw ? SBLOCK : BLOCK;                // threads per block of the main kernel
-    int sunr = env_int("FUSE_OUTER_SUNR", 2);                     // steps of a wave whose gathers leave together (stationary form)
+    int sunr = env_int("FUSE_OUTER_SUNR", SBLOCK > 512 ? 1 : 2);  // steps of a wave whose gathers leave together (stationary form)
     sunr = (sunr >= 2 && G % 2 == 0) ? 2 : 1;
     const std::string key = std::string("outer|") + (panels ? (stat_rcw ? "stat" + std::to_string(stat_rcw) + "r" + std::to_string(r) + "u" + std::to_string(sunr) + "|"
                                                              : flat_rc ? "flat" + std::to_string(flat_rc) + "r" + std::to_string(r) + "w" + std::to_string(flat_wpe) + "|" : std::string("panels|")) : std::string("")) + prog.key + "|" + side_key(sides, nsides) + "|agg" +
