@@ -1356,7 +1356,8 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
     const int KBLOCK = stat_rcw ? SBLOCK : BLOCK;                // threads per block of the main kernel
     int sunr = env_int("FUSE_OUTER_SUNR", SBLOCK > 512 ? 1 : 2);  // steps of a wave whose gathers leave together (stationary form)
     sunr = (sunr >= 2 && G % 2 == 0) ? 2 : 1;
-    const std::string key = std::string("outer|") + (panels ? (stat_rcw ? "stat" + std::to_string(stat_rcw) + "r" + std::to_string(r) + "u" + std::to_string(sunr) + "|"
+    const int uq = std::max(1, std::min(16, env_int("FUSE_OUTER_UQ", 4)));      // vectors of U per thread in flight while the rows are staged
+    const std::string key = std::string("outer|") + (panels ? (stat_rcw ? "stat" + std::to_string(stat_rcw) + "r" + std::to_string(r) + "u" + std::to_string(sunr) + "q" + std::to_string(uq) + "|"
                                                              : flat_rc ? "flat" + std::to_string(flat_rc) + "r" + std::to_string(r) + "w" + std::to_string(flat_wpe) + "|" : std::string("panels|")) : std::string("")) + prog.key + "|" + side_key(sides, nsides) + "|agg" +
                             std::to_string(kmode) + (transposed ? "T" : "") + (kmode == 2 && out_vec ? "o" : "") + "|v" + std::to_string(VEC) + "g" + std::to_string(G) + "e" +
                             std::to_string(EPL) + "u" + std::to_string(UNR) + "b" + std::to_string(KBLOCK) + "w" +
@@ -1374,7 +1375,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
              "\n#define FUSE_NEED_COL " + std::to_string(need_col) + "\n#define FUSE_PANELS " + std::to_string(panels ? (stat_rcw ? 3 : flat_rc ? 2 : 1) : 0) +
              "\n#define FUSE_RANK " + std::to_string(r) + "\n#define FUSE_RC " + std::to_string(std::max(flat_rc, 1)) +
              "\n#define FUSE_RB " + std::to_string(std::max(stat_rcw, 1)) + "\n#define FUSE_SUNR " + std::to_string(sunr) +
-             "\n#define FUSE_WPE " + std::to_string(stat_rcw ? SBLOCK / 256 : flat_wpe) + "\n";
+             "\n#define FUSE_WPE " + std::to_string(stat_rcw ? SBLOCK / 256 : flat_wpe) + "\n#define FUSE_UQ " + std::to_string(uq) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_outer_body(prog);
         s += kSrcOuter;
@@ -1474,7 +1475,7 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         A.npanels = npanels;
         A.panel_w = panel_w;
         A.panel_ptr = ws.partials + part_doubles;
-        const int64_t gp = (X->rows * 16 + 255) / 256;
+        const int64_t gp = (X->rows * 16 + 255) / 256;                 // 16 lanes per row
         if ((rc = rt.launch(fn.prep, (unsigned)gp, 1, 256, stream, &A, sizeof A, g_err)))
             return rc;
     }
