@@ -30,7 +30,10 @@
  *     whose plan is cached and loaded and whose workspace is large enough only
  *     launches kernels (outputs are cleared by a fill kernel, arrival counters
  *     reset themselves), so after one warm-up call on the capturing stream a
- *     sequence of calls can be recorded into a HIP graph and replayed.
+ *     sequence of calls can be recorded into a HIP graph and replayed.  A call
+ *     that still has to compile or to allocate while its stream is being
+ *     captured fails (FUSE_ENOMEM / FUSE_ERUNTIME: the runtime refuses the
+ *     allocation) and the capture is lost: warm up first.
  *   - Return value: FUSE_OK (0) or a negative fuse_status; on error nothing is
  *     enqueued and `fuse_last_error()` returns a thread-local message
  *     (including the hipRTC log for FUSE_ECOMPILE).
