@@ -55,7 +55,9 @@ public:
                 return 0;
             }
         }
-        const std::string name = name_prefix + "_" + hash_hex(key);
+        // The kernel's name carries a hash of the key AND of the source text (generated once under a stand-in
+        // name): a profile taken of a kernel names exactly the code it measured.
+        const std::string name = name_prefix + "_" + hash_hex(key + "\n" + make_source(name_prefix + "_unnamed"));
         auto p = std::make_shared<Plan>();
         p->kernel_name = name;
         p->source = make_source(name);
