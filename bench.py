@@ -216,6 +216,19 @@ def sweep(args):
             if "magg_sparse" in only:
                 report("8d", "MAgg sum(X*Y), sum(X*Z), X sparse 0.1", [m, n],
                        timed(lambda: F.fuse_magg_csr(XY_XZ, xs, sd)), 28 * nnz + 4 * m, nnz)
+            if only & {"cell_sparse", "magg_sparse"}:
+                # the figures' own setting: Y and Z sparse as well (12 bytes per stored cell and 4 per row of each matrix)
+                ys, nny = dev_csr(m, n, 0.1, 12)
+                zs, nnzz = dev_csr(m, n, 0.1, 14)
+                ssd = [("sparse", ys), ("sparse", zs)]
+                sp_bytes = 12 * (nnz + nny + nnzz) + 12 * m
+                if "cell_sparse" in only:
+                    report("8b", "Cell sum(X*Y*Z), X, Y, Z sparse 0.1", [m, n],
+                           timed(lambda: F.fuse_cell_csr(XYZ, xs, ssd, "full")), sp_bytes, nnz)
+                if "magg_sparse" in only:
+                    report("8d", "MAgg sum(X*Y), sum(X*Z), X, Y, Z sparse 0.1", [m, n],
+                           timed(lambda: F.fuse_magg_csr(XY_XZ, xs, ssd)), sp_bytes, nnz)
+                del ys, zs, ssd
             if "row_sparse" in only:
                 report("8f", "Row t(X)(Xv), X sparse 0.1", [m, n],
                        timed(lambda: F.fuse_row(TXV, xs, [("rowvec", v)], "col_t")), 12 * nnz + 4 * m + 16 * n, nnz)

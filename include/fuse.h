@@ -84,7 +84,12 @@ typedef enum {
     FUSE_SIDE_SCALAR = 3,   /* host scalar in `scalar`; passed as a kernel argument   */
     /* Row bodies only (Sec. 2.2 Row listing, vectMatMult / getVector): */
     FUSE_SIDE_RHS = 4,      /* cols(X) x k right-hand side of FUSE_OP_MATMULT, 1 <= k <= 16 */
-    FUSE_SIDE_KVEC = 5      /* rows(X) x k: row rix is a k-vector (data[rix * ld + j])       */
+    FUSE_SIDE_KVEC = 5,     /* rows(X) x k: row rix is a k-vector (data[rix * ld + j])       */
+    /* Sparse side input (Table 1: Cell, MAgg and Row bind to sparse / dense side inputs; Sec. 5.2,
+     * "Cell Operations": sparse lookups behind getValue()).  Calls over a CSR main input only
+     * (fuse_cell_csr, fuse_magg_csr, fuse_row with Xs), bodies without k-vectors: */
+    FUSE_SIDE_SPARSE = 6    /* rows x cols as the main input, stored as CSR in `sp`: the value at
+                               (rix, cix) is the stored one, or 0 where nothing is stored   */
 } fuse_side_kind;
 
 #define FUSE_MAX_K 16
@@ -97,7 +102,7 @@ typedef struct {
 
 /* CSR with sorted, distinct column indices per row.  Every STORED entry is
  * processed, whatever its value (Table 1: the binding is to the stored cells). */
-typedef struct {
+typedef struct fuse_csr_ {
     const double *vals;     /* device, nnz values                                     */
     const int32_t *colidx;  /* device, nnz column indices in [0, cols)                */
     const void *rowptr;     /* device, rows+1 offsets, int32 or int64                 */
@@ -111,6 +116,8 @@ typedef struct {
     fuse_dense m;           /* MATRIX: rows x cols, ld; COLVEC: rows x 1, ld = stride
                                between consecutive rows' values; ROWVEC: 1 x cols     */
     double scalar;          /* SCALAR only                                            */
+    const struct fuse_csr_ *sp; /* SPARSE only: the side matrix (host struct, device arrays; sorted, distinct
+                               column indices per row, as for a main input); NULL otherwise.  `m` is not read. */
 } fuse_side;
 
 /* Postfix expression tokens. */

@@ -20,7 +20,8 @@ class CsrDesc(ctypes.Structure):
 
 
 class Side(ctypes.Structure):
-    _fields_ = [("kind", ctypes.c_int32), ("m", Dense), ("scalar", ctypes.c_double)]
+    _fields_ = [("kind", ctypes.c_int32), ("m", Dense), ("scalar", ctypes.c_double),
+                ("sp", ctypes.POINTER(CsrDesc))]
 
 
 class Tok(ctypes.Structure):

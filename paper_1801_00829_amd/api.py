@@ -5,7 +5,7 @@ from collections import namedtuple
 from . import _lib as L
 
 AGG = {"none": 0, "full": 1, "row": 2, "col": 3, "col_t": 4, "right_mm": 5, "left_mm": 6}
-SIDE = {"matrix": 0, "colvec": 1, "rowvec": 2, "scalar": 3, "rhs": 4, "kvec": 5}
+SIDE = {"matrix": 0, "colvec": 1, "rowvec": 2, "scalar": 3, "rhs": 4, "kvec": 5, "sparse": 6}
 OPS = {
     "main": 1, "side": 2, "const": 3, "uvdot": 4,
     "neg": 16, "abs": 17, "sqrt": 18, "exp": 19, "log": 20, "pow2": 21, "sign": 22, "neq0": 23,
@@ -96,10 +96,15 @@ def _sides(sides, m, n):
     """[(kind, tensor | float | shape-tuple)] -> (Side array, count)."""
     import torch
     arr = (L.Side * max(len(sides), 1))()
+    arr._keep = []                                        # CSR descriptors of sparse sides live as long as the array
     for k, (kind, val) in enumerate(sides):
         arr[k].kind = SIDE[kind]
         if kind == "scalar":
             arr[k].scalar = float(val)
+        elif kind == "sparse":                            # a Csr of device tensors, or prepare_*: (is64, None, nnz, shape)
+            desc = _csr(val)
+            arr._keep.append(desc)
+            arr[k].sp = ctypes.pointer(desc)
         elif kind in ("rhs", "kvec"):
             if isinstance(val, tuple):                    # shape only: (rows, k)
                 arr[k].m = L.Dense(None, int(val[0]), int(val[1]), int(val[1]))

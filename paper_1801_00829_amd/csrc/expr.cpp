@@ -88,7 +88,7 @@ int parse_program(Tmpl t, const fuse_expr *exprs, int k, const fuse_side *sides,
                     prog.kdim = kd;
                     nd.kind = kind == FUSE_SIDE_RHS ? KIND_M : KIND_K;
                 } else {
-                    nd.kind = (row && (kind == FUSE_SIDE_MATRIX || kind == FUSE_SIDE_ROWVEC)) ? KIND_V : KIND_S;
+                    nd.kind = (row && (kind == FUSE_SIDE_MATRIX || kind == FUSE_SIDE_SPARSE || kind == FUSE_SIDE_ROWVEC)) ? KIND_V : KIND_S;
                 }
                 prog.side_used[tk.arg] = true;
             } else if (tk.op == FUSE_OP_CONST) {

@@ -28,6 +28,8 @@ typedef struct {
                                                  after the panel's first column ((npanels+1) x m offsets)         */
     int panel_w;                              /* Outer: columns per panel             */
     int pad_;
+    const int *side_ci[FUSE_MAX_SIDES];       /* sparse side inputs: column indices (values in side[], stored  */
+    const void *side_rp[FUSE_MAX_SIDES];      /*   cells in side_ld[]), row offsets (int32 or int64)           */
 } fuse_kargs;
 
 #endif

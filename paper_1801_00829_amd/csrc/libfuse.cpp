@@ -145,7 +145,7 @@ struct SideInfo {
 
 // Shape checks shared by all templates: side k against an m x n main input.
 int check_sides(const fuse_side *sides, int nsides, int64_t m, int64_t n, bool need_data,
-                const bool *used)
+                const bool *used, bool sparse_ok = false)
 {
     if (nsides < 0 || nsides > FUSE_MAX_SIDES)
         return fail(FUSE_EINVAL, "nsides must be in [0, " + std::to_string(FUSE_MAX_SIDES) + "]");
@@ -187,6 +187,20 @@ int check_sides(const fuse_side *sides, int nsides, int64_t m, int64_t n, bool n
             if (s.m.ld < s.m.cols)
                 return fail(FUSE_ESHAPE, at + "ld < cols");
             break;
+        case FUSE_SIDE_SPARSE: {
+            if (!sparse_ok)
+                return fail(FUSE_EUNSUPPORTED, at + "sparse side inputs go with a CSR main input (fuse_cell_csr, fuse_magg_csr, fuse_row with Xs)");
+            const fuse_csr *c = s.sp;
+            if (!c)
+                return fail(FUSE_EINVAL, at + "sp is NULL");
+            if (c->rows != m || c->cols != n)
+                return fail(FUSE_ESHAPE, at + "sparse side must be " + std::to_string(m) + " x " + std::to_string(n));
+            if (c->nnz < 0 || (!c->rowptr_is64 && c->nnz > 2147483647LL))
+                return fail(FUSE_EINVAL, at + "bad nnz for the offset width");
+            if (need_data && used[k] && (!c->rowptr || (c->nnz > 0 && (!c->vals || !c->colidx))) && m > 0)
+                return fail(FUSE_EINVAL, at + "array pointer of the sparse side is NULL");
+            continue;
+        }
         default:
             return fail(FUSE_EINVAL, at + "unknown side kind " + std::to_string(s.kind));
         }
@@ -237,6 +251,9 @@ std::string side_tables(const fuse_side *sides, int nsides, const bool *used)
     s += "-1};\nstatic __device__ constexpr bool fuse_side_used[] = {";
     for (int k = 0; k < nsides; ++k)
         s += std::string(used[k] ? "true" : "false") + ", ";
+    s += "false};\nstatic __device__ constexpr bool fuse_side_rp64[] = {";      // sparse sides: 64-bit row offsets
+    for (int k = 0; k < nsides; ++k)
+        s += std::string(sides[k].kind == FUSE_SIDE_SPARSE && sides[k].sp && sides[k].sp->rowptr_is64 ? "true" : "false") + ", ";
     s += "false};\n";
     return s;
 }
@@ -244,14 +261,24 @@ std::string side_tables(const fuse_side *sides, int nsides, const bool *used)
 std::string side_key(const fuse_side *sides, int nsides)
 {
     std::string s = "sides:";
-    for (int k = 0; k < nsides; ++k)
+    for (int k = 0; k < nsides; ++k) {
         s += std::to_string(sides[k].kind);
+        if (sides[k].kind == FUSE_SIDE_SPARSE)
+            s += (sides[k].sp && sides[k].sp->rowptr_is64) ? "L" : "l";
+    }
     return s;
 }
 
 void fill_side_args(fuse_kargs &A, const fuse_side *sides, int nsides)
 {
     for (int k = 0; k < nsides; ++k) {
+        if (sides[k].kind == FUSE_SIDE_SPARSE && sides[k].sp) {
+            A.side[k] = sides[k].sp->vals;
+            A.side_ci[k] = sides[k].sp->colidx;
+            A.side_rp[k] = sides[k].sp->rowptr;
+            A.side_ld[k] = sides[k].sp->nnz;                  // bound of every offset read from side_rp
+            continue;
+        }
         A.side[k] = sides[k].m.data;
         A.side_ld[k] = sides[k].kind == FUSE_SIDE_ROWVEC ? 0 : sides[k].m.ld;
         A.side_scalar[k] = sides[k].scalar;
@@ -311,7 +338,7 @@ bool mfma_pattern(const Program &prog, const fuse_side *sides, int nsides, int &
     if (v.op != FUSE_OP_SIDE || v.arg < 0 || v.arg >= nsides || sides[v.arg].kind != FUSE_SIDE_RHS)
         return false;
     for (int q = 0; q < nsides; ++q)
-        if (prog.side_used[q] && (sides[q].kind == FUSE_SIDE_MATRIX || sides[q].kind == FUSE_SIDE_ROWVEC))
+        if (prog.side_used[q] && (sides[q].kind == FUSE_SIDE_MATRIX || sides[q].kind == FUSE_SIDE_SPARSE || sides[q].kind == FUSE_SIDE_ROWVEC))
             return false;
     vside = v.arg;
     return true;
@@ -742,9 +769,12 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
         // shape checks need to know which sides are used; parse first with kinds only
         if (nsides < 0 || nsides > FUSE_MAX_SIDES || (nsides > 0 && !sides))
             return fail(FUSE_EINVAL, "bad sides / nsides");
-        for (int q = 0; q < nsides; ++q)
+        for (int q = 0; q < nsides; ++q) {
+            if (sides[q].kind == FUSE_SIDE_SPARSE)
+                return fail(FUSE_EUNSUPPORTED, "side " + std::to_string(q) + ": sparse side inputs go with a CSR main input (fuse_cell_csr, fuse_magg_csr)");
             if (sides[q].kind < 0 || sides[q].kind > 3)
                 return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
+        }
         rc = parse_cached(Tmpl::CELL, exprs, k, sides, nsides, prog, g_err);
         if (rc)
             return rc;
@@ -922,7 +952,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     // run the streaming skeleton's flat form over the cell arrays, whatever the row lengths
     bool need_rid = prog.nred > 0 || ac == 2 || !prog.result_vec;
     for (int k = 0; k < nsides; ++k)
-        need_rid |= prog.side_used[k] && (sides[k].kind == FUSE_SIDE_MATRIX || sides[k].kind == FUSE_SIDE_COLVEC);
+        need_rid |= prog.side_used[k] && (sides[k].kind == FUSE_SIDE_MATRIX || sides[k].kind == FUSE_SIDE_SPARSE || sides[k].kind == FUSE_SIDE_COLVEC);
     // (bodies with k-vectors run in the lane-group form only)
     const double mean_len = m > 0 ? (double)X->nnz / (double)m : 0.0;
     // LDS the streaming form needs per block beside column sums and staged row vectors: a histogram of
@@ -946,6 +976,29 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
     const int64_t npad = (cols_lds || stage_rv) ? std::max<int64_t>(n, 1) : 1;
     const int64_t naccpad = cols_lds ? std::max<int64_t>(n * nacck, 1) : 1;
 
+    // Sparse side inputs in the lane-group form: every group stages the column indices of the side's row in LDS
+    // (FUSE_SCAP entries per group and side: 1.5 x the side's mean row length, a power of two, while it fits
+    // beside the column sums and the staged row vectors); longer rows of a side are searched in memory.
+    int nsparse = 0, scap = 0;
+    if (!streaming) {
+        double longest = 0.0;
+        for (int k = 0; k < nsides; ++k)
+            if (prog.side_used[k] && sides[k].kind == FUSE_SIDE_SPARSE && sides[k].sp) {
+                ++nsparse;
+                longest = std::max(longest, m > 0 ? (double)sides[k].sp->nnz / (double)m : 0.0);
+            }
+        if (nsparse > 0 && env_int("FUSE_CSR_SCAP", -1) != 0) {
+            scap = std::min(1024, std::max(G, next_pow2((int64_t)(1.5 * longest + 8.0))));
+            if (env_int("FUSE_CSR_SCAP", -1) > 0)
+                scap = std::min(1024, next_pow2(env_int("FUSE_CSR_SCAP", -1)));
+            const int64_t used = ((cols_lds ? naccpad : 0) + (stage_rv ? (int64_t)nrv * npad : 0)) * 8 + 8192;
+            while (scap >= 8 && (int64_t)(BLOCK / G) * nsparse * scap * 4 > lds_budget - used)
+                scap >>= 1;
+            if (scap < 8)
+                scap = 0;
+        }
+    }
+
     const int nt = env_int("FUSE_CSR_NT", streaming ? 1 : 0);
     // lane-group form: the rows are dealt to the blocks in pieces of FUSE_CSR_ILV steps of a block (default 1:
     // 256 rows with 16 rows per wave and 16 waves), round-robin, when every block gets at least four pieces;
@@ -968,7 +1021,7 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
                                                             : "|g" + std::to_string(G) + "c" + std::to_string(C) + "r" + std::to_string(RS)) + "b" +
                             std::to_string(BLOCK) + "p" + std::to_string(npad) + "a" + std::to_string(naccpad) + "s" + std::to_string(stage_rv) + (cols_global ? "G" : "") +
                             "w" + std::to_string(X->rowptr_is64 != 0) + std::to_string(m < (1LL << 30)) + "nt" +
-                            std::to_string(nt) + "i" + std::to_string(ilv);
+                            std::to_string(nt) + "i" + std::to_string(ilv) + (scap ? "sp" + std::to_string(nsparse) + "x" + std::to_string(scap) : "");
     std::shared_ptr<Plan> plan;
     int rc = rt.plan(key, name_prefix, [&](const std::string &name) {
         std::string s = kSrcArgs;
@@ -985,7 +1038,8 @@ int row_csr_impl(const Program &prog, const fuse_csr *X, const fuse_side *sides,
              "\n#define FUSE_RP64 " + std::to_string(X->rowptr_is64 != 0) + "\n#define FUSE_ROW32 " +
              std::to_string(m < (1LL << 30)) + "\n#define FUSE_NPAD " +
              std::to_string(npad) + "\n#define FUSE_NACCPAD " + std::to_string(naccpad) + "\n#define FUSE_STAGE_RV " + std::to_string(stage_rv) +
-             "\n#define FUSE_NRV " + std::to_string(std::max(nrv, 1)) + "\n";
+             "\n#define FUSE_NRV " + std::to_string(std::max(nrv, 1)) + "\n#define FUSE_NSPARSE " + std::to_string(std::max(nsparse, 1)) +
+             "\n#define FUSE_SCAP " + std::to_string(scap) + "\n";
         s += side_tables(sides, nsides, prog.side_used);
         s += emit_row_body(prog);
         s += streaming ? kSrcRowCsrStream : kSrcRowCsr;
@@ -1075,7 +1129,7 @@ int cell_csr_impl(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
     if (nsides < 0 || nsides > FUSE_MAX_SIDES || (nsides > 0 && !sides))
         return fail(FUSE_EINVAL, "bad sides / nsides");
     for (int q = 0; q < nsides; ++q)
-        if (sides[q].kind < 0 || sides[q].kind > 3)
+        if (sides[q].kind < 0 || (sides[q].kind > 3 && sides[q].kind != FUSE_SIDE_SPARSE))
             return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
     Program cprog, prog;
     if ((rc = parse_cached(Tmpl::CELL, exprs, k, sides, nsides, cprog, g_err)))     // Cell tokens only
@@ -1084,7 +1138,7 @@ int cell_csr_impl(const fuse_expr *exprs, int k, const fuse_csr *X, const fuse_s
         return rc;
     if (!prog.result_vec)
         return fail(FUSE_EDESC, "not sparse-safe: the body does not depend on the main input");
-    if ((rc = check_sides(sides, nsides, X->rows, X->cols, launch, prog.side_used)))
+    if ((rc = check_sides(sides, nsides, X->rows, X->cols, launch, prog.side_used, true)))
         return rc;
     const int64_t count = ac == 1 ? k : ac == 2 ? X->rows : ac == 3 ? X->cols : X->nnz;
     if (launch && !out && count > 0)
@@ -1110,14 +1164,17 @@ int row_impl(const fuse_expr *expr, const fuse_dense *Xd, const fuse_csr *Xs, co
     if (nsides < 0 || nsides > FUSE_MAX_SIDES || (nsides > 0 && !sides))
         return fail(FUSE_EINVAL, "bad sides / nsides");
     for (int q = 0; q < nsides; ++q)
-        if (sides[q].kind < 0 || sides[q].kind > FUSE_SIDE_KVEC)
+        if (sides[q].kind < 0 || sides[q].kind > FUSE_SIDE_SPARSE)
             return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
     Program prog;
     if ((rc = parse_cached(Xd ? Tmpl::ROW_DENSE : Tmpl::ROW_CSR, expr, 1, sides, nsides, prog, g_err)))
         return rc;
     const int64_t m = Xd ? Xd->rows : Xs->rows, n = Xd ? Xd->cols : Xs->cols;
-    if ((rc = check_sides(sides, nsides, m, n, launch, prog.side_used)))
+    if ((rc = check_sides(sides, nsides, m, n, launch, prog.side_used, Xs != nullptr)))
         return rc;
+    for (int q = 0; q < nsides; ++q)
+        if (sides[q].kind == FUSE_SIDE_SPARSE && prog.side_used[q] && prog.kdim > 0)
+            return fail(FUSE_EUNSUPPORTED, "side " + std::to_string(q) + ": sparse side inputs are not built for bodies with k-vectors");
     {
         const int ac = agg_code(agg);
         const int64_t cells = Xd ? m * n : Xs->nnz;
@@ -1205,9 +1262,12 @@ int outer_impl(const fuse_expr *expr, const fuse_csr *X, const fuse_dense *U, co
         return fail(FUSE_EUNSUPPORTED, "Outer rank must be in [1, 1024]");
     if (nsides < 0 || nsides > FUSE_MAX_SIDES || (nsides > 0 && !sides))
         return fail(FUSE_EINVAL, "bad sides / nsides");
-    for (int q = 0; q < nsides; ++q)
+    for (int q = 0; q < nsides; ++q) {
+        if (sides[q].kind == FUSE_SIDE_SPARSE)
+            return fail(FUSE_EUNSUPPORTED, "side " + std::to_string(q) + ": Outer binds to dense side inputs (Table 1)");
         if (sides[q].kind < 0 || sides[q].kind > 3)
             return fail(FUSE_EINVAL, "side " + std::to_string(q) + ": unknown side kind");
+    }
     Program prog;
     if ((rc = parse_cached(Tmpl::OUTER, expr, 1, sides, nsides, prog, g_err)))
         return rc;

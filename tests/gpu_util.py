@@ -15,6 +15,8 @@ def dev_sides(sides):
     for kind, val in sides:
         if kind == "scalar":
             out.append((kind, float(np.asarray(val).reshape(-1)[0])))
+        elif kind == "sparse":                     # (rowptr, colidx, vals, shape[, rowptr64]) on the host
+            out.append((kind, dev_csr(*val)))
         else:
             out.append((kind, to_dev(np.asarray(val, dtype=np.float64))))
     return out

@@ -859,6 +859,100 @@ def test_sparse_cell_paper_expression_and_rejections(csr_mapping):
         assert e.value.code == -3
 
 
+# ------------------------------------------------------- sparse side inputs ---
+
+def _sparse_side(m, n, dens, seed, rowptr64=False):
+    """A CSR side input for the GPU and the same matrix densified for the oracle (whose operators take the side
+    as the matrix it is: a value per cell, 0 where nothing is stored)."""
+    rp, ci, va = W.csr_bernoulli(m, n, dens, seed)
+    dense = ops.csr_to_dense(ops.make_csr(rp, ci, va, (m, n))) if m * n else np.zeros((m, n))
+    return ("sparse", (rp, ci, va, (m, n), rowptr64)), ("matrix", dense)
+
+
+@pytest.mark.parametrize("case", range(10 * MORE))
+def test_sparse_side_inputs_random_expressions(case, csr_mapping):
+    """Cell, MAgg and Row bodies over a CSR main input whose matrix side input is sparse as well (Table 1: sparse /
+    dense side inputs; Fig. 8b / 8d): every result against the oracle's operator-at-a-time plan on the densified side."""
+    import paper_1801_00829_amd as F
+    rng = np.random.default_rng(9900 + case)
+    m, n = [(1, 1), (37, 19), (300, 1000), (1000, 100), (64, 3000)][case % 5]
+    dens = [1.0, 0.3, 0.1, 0.02, 0.004][case % 5]
+    sdens = [1.0, 0.5, 0.1, 0.3, 0.01][(case + 2) % 5]
+    rp, ci, va = W.csr_bernoulli(m, n, dens, 9900 + case)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    gpu_side, ref_side = _sparse_side(m, n, sdens, 19900 + case, rowptr64=bool(case % 2))
+    rest = _sides(rng, m, n)[1:]
+    sides, gsides = [ref_side] + rest, [gpu_side] + rest
+    xd, sd = dev_csr(rp, ci, va, (m, n)), dev_sides(gsides)
+    exprs = [random_row_expr(rng, KINDS, depth=3, want="V", sparse_safe=True, reductions=False) for _ in range(3)]
+    exprs[0] = [("main",), ("side", 0), ("mul",)] + exprs[0] + [("mul",)]          # the sparse side is in every run
+    for agg in ("none", "row", "col", "full"):
+        print("sparse side cell case", case, (m, n), agg, exprs[0], flush=True)
+        got = host(F.fuse_cell_csr(exprs[0], xd, sd, agg))
+        ref = unfused.cell_csr(exprs[0], x, sides, agg)
+        a = np.abs(np.nan_to_num(unfused.cell_csr(exprs[0], x, sides, "none"), nan=0, posinf=0, neginf=0))
+        scale = {"none": None, "full": a.sum(), "row": ops.csr_row_sums(x, a).max(initial=0.0),
+                 "col": ops.csr_col_sums(x, a).max(initial=0.0)}[agg]
+        assert_close(got, ref, scale=None if scale is None else max(scale, 1e-300), what="sparse side cell %s" % agg)
+    got = host(F.fuse_magg_csr(exprs, xd, sd))
+    ref = unfused.magg_csr(exprs, x, sides)
+    for j in range(3):
+        a = np.abs(np.nan_to_num(unfused.cell_csr(exprs[j], x, sides, "none"), nan=0, posinf=0, neginf=0))
+        assert_close(got[j], ref[j], scale=max(a.sum(), 1e-300), what="sparse side magg[%d]" % j)
+    # a Row body with row aggregates
+    expr = [("main",), ("side", 0), ("mul",)] + random_row_expr(rng, KINDS, depth=3, want="V", sparse_safe=True) + [("mul",)]
+    none_ref = unfused.row_csr(expr, x, sides, "none")
+    a = np.abs(np.nan_to_num(none_ref, nan=0.0, posinf=0.0, neginf=0.0))
+    for agg in ("none", "row", "col_t", "full"):
+        print("sparse side row case", case, (m, n), agg, expr, flush=True)
+        got = host(F.fuse_row(expr, xd, sd, agg))
+        ref = unfused.row_csr(expr, x, sides, agg)
+        scale = {"none": None, "full": a.sum(), "row": ops.csr_row_sums(x, a).max(initial=0.0),
+                 "col_t": ops.csr_col_sums(x, a).max(initial=0.0)}[agg]
+        assert_close(got, ref, scale=None if scale is None else max(scale, 1e-300), what="sparse side row %s" % agg)
+
+
+def test_sparse_side_inputs_paper_expression_and_rejections(csr_mapping):
+    """sum(X * Y * Z) with X, Y and Z sparse (Fig. 8b; density 0.1): the oracle's plan on the densified matrices, the
+    dense-side operator on the same values, and the calls that do not take a sparse side."""
+    import paper_1801_00829_amd as F
+    from oracle import plans
+    m, n = 2000, 1000
+    rp, ci, va = W.csr_bernoulli(m, n, 0.1, 91)
+    (ky, ysp), (_, yd) = _sparse_side(m, n, 0.1, 92)
+    (kz, zsp), (_, zd) = _sparse_side(m, n, 0.1, 93, rowptr64=True)
+    xd = dev_csr(rp, ci, va, (m, n))
+    expr = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+    sd = dev_sides([(ky, ysp), (kz, zsp)])
+    dense = ops.csr_to_dense(ops.make_csr(rp, ci, va, (m, n)))
+    got = host(F.fuse_cell_csr(expr, xd, sd, "full"))
+    assert_close(got, plans.cell_sum_xyz(dense, yd, zd), scale=np.abs(dense * yd * zd).sum(), what="sum(XYZ), all sparse")
+    dsd = [("matrix", to_dev(yd)), ("matrix", to_dev(zd))]
+    assert_close(got, host(F.fuse_cell_csr(expr, xd, dsd, "full")), tol=1e-12, what="sparse against dense sides")
+    two = host(F.fuse_magg_csr([expr[:3], [("main",), ("side", 1), ("mul",)]], xd, sd))
+    assert_close(two[0], (dense * yd).sum(), scale=np.abs(dense * yd).sum(), what="sum(XY), sparse")
+    assert_close(two[1], (dense * zd).sum(), scale=np.abs(dense * zd).sum(), what="sum(XZ), sparse")
+    # an empty side: every product is zero
+    empty = ("sparse", (np.zeros(m + 1, np.int64), np.zeros(0, np.int32), np.zeros(0), (m, n)))
+    assert host(F.fuse_cell_csr(expr, xd, dev_sides([empty, (kz, zsp)]), "full"))[0] == 0.0
+    # calls that bind to dense side inputs only
+    with pytest.raises(F.FuseError) as e:
+        F.fuse_cell(expr, to_dev(dense), sd, "full")
+    assert e.value.code == -7
+    u = to_dev(np.ones((m, 3)))
+    v = to_dev(np.ones((n, 3)))
+    with pytest.raises(F.FuseError) as e:
+        F.fuse_outer([("main",), ("uvdot",), ("mul",), ("side", 0), ("mul",)], xd, u, v, sd[:1], "full")
+    assert e.value.code == -7
+    with pytest.raises(F.FuseError) as e:
+        F.fuse_row(expr, to_dev(dense), sd, "full")
+    assert e.value.code == -7
+    wrong = dev_sides([_sparse_side(m, n + 1, 0.1, 94)[0]])
+    with pytest.raises(F.FuseError) as e:
+        F.fuse_cell_csr(expr[:3], xd, wrong, "full")
+    assert e.value.code == -2
+
+
 # ------------------------------------------- Row with a matrix right-hand side ---
 
 MLOG_Q = [("side", 1), ("main",), ("side", 0), ("matmult",), ("mul",)]                   # Q = P * (X V)

@@ -163,6 +163,56 @@ def test_shape_and_argument_errors(F):
                                       ctypes.byref(L.Dense(None, 6, 3, 3)), None, 0, mm) == 0
 
 
+def test_sparse_side_inputs_host_checks(F):
+    """FUSE_SIDE_SPARSE: compiles for the calls over a CSR main input, is refused elsewhere, and its descriptor is
+    checked on the host (no GPU needed)."""
+    from paper_1801_00829_amd import _lib as L
+    lib = L.load()
+    hdr = open(os.path.join(ROOT, "include", "fuse.h")).read()
+    assert re.search(r"FUSE_SIDE_SPARSE\s*=\s*6", hdr) and F.api.SIDE["sparse"] == 6
+    shape, nnz = (300, 200), 6000
+    sp = (0, None, 5000, shape)
+    # sum(X * Y * Z), X, Y, Z sparse: Cell, MAgg and Row over a CSR main input
+    F.prepare_cell_csr(XYZ, shape, nnz, [("sparse", sp), ("sparse", (1, None, 7000, shape))], "full")
+    src = F.last_source()
+    assert "fuse_side_kind[] = {6, 6, -1}" in src and "fuse_side_rp64[] = {false, true, false}" in src
+    F.prepare_magg_csr([XYZ[:3], [("main",), ("side", 1), ("mul",)]], shape, nnz, [("sparse", sp), ("sparse", sp)])
+    F.prepare_row([("main",), ("side", 0), ("mul",), ("rowsum",), ("main",), ("mul",)], shape, [("sparse", sp)], "col_t",
+                  nnz=nnz)
+    # 32- and 64-bit offsets of the side are different kernels
+    k32 = (F.prepare_cell_csr(XYZ[:3], shape, nnz, [("sparse", sp)], "full"), F.last_kernel())[1]
+    k64 = (F.prepare_cell_csr(XYZ[:3], shape, nnz, [("sparse", (1, None, 5000, shape))], "full"), F.last_kernel())[1]
+    assert k32 != k64
+    # refused: dense main inputs, Outer, bodies with k-vectors
+    for call in (lambda: F.prepare_cell(XYZ, shape, [("sparse", sp), ("sparse", sp)], "full"),
+                 lambda: F.prepare_magg([XYZ], shape, [("sparse", sp), ("sparse", sp)]),
+                 lambda: F.prepare_row(XYZ, shape, [("sparse", sp), ("sparse", sp)], "full"),
+                 lambda: F.prepare_outer([("main",), ("uvdot",), ("mul",), ("side", 0), ("mul",)], shape, 4, nnz,
+                                         [("sparse", sp)], "full"),
+                 lambda: F.prepare_row([("main",), ("side", 1), ("mul",), ("main",), ("side", 0), ("matmult",), ("outerk",)],
+                                       shape, [("rhs", (shape[1], 3)), ("sparse", sp)], "col_t", nnz=nnz)):
+        with pytest.raises(F.FuseError) as e:
+            call()
+        assert e.value.code == -7, str(e.value)
+    # the descriptor: NULL, wrong shape, too many cells for 32-bit offsets
+    e_, keep = F.api._expr(XYZ[:3])
+    xs = L.CsrDesc(None, None, None, 0, shape[0], shape[1], nnz)
+    sides = (L.Side * 1)()
+    sides[0].kind = 6
+    assert lib.fuse_prepare_cell_csr(ctypes.byref(e_), ctypes.byref(xs), sides, 1, 1) == -1
+    assert b"sp is NULL" in lib.fuse_last_error()
+    bad = L.CsrDesc(None, None, None, 0, shape[0], shape[1] + 1, 10)
+    sides[0].sp = ctypes.pointer(bad)
+    assert lib.fuse_prepare_cell_csr(ctypes.byref(e_), ctypes.byref(xs), sides, 1, 1) == -2
+    bad = L.CsrDesc(None, None, None, 0, shape[0], shape[1], 1 << 31)
+    sides[0].sp = ctypes.pointer(bad)
+    assert lib.fuse_prepare_cell_csr(ctypes.byref(e_), ctypes.byref(xs), sides, 1, 1) == -1
+    # a launching call wants the side's arrays
+    good = L.CsrDesc(None, None, None, 0, shape[0], shape[1], 10)
+    sides[0].sp = ctypes.pointer(good)
+    assert lib.fuse_prepare_cell_csr(ctypes.byref(e_), ctypes.byref(xs), sides, 1, 1) == 0
+
+
 def test_row_type_checking_and_sparse_safety(F):
     dot_v = [("main",), ("side", 0), ("dot",)]
     F.prepare_row(dot_v, (100, 10), [("rowvec", None)], "none")            # scalar result, per row
