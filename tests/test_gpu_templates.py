@@ -953,6 +953,31 @@ def test_sparse_side_inputs_paper_expression_and_rejections(csr_mapping):
     assert e.value.code == -2
 
 
+@pytest.mark.parametrize("scap", ["0", "8", "64"])
+def test_sparse_side_lookup_paths_agree(scap, monkeypatch):
+    """The three ways a cell finds its value in a sparse side -- the side's row staged in LDS, a side row too long for
+    its LDS slot, every look-up in memory -- against the oracle and against each other (lane-group kernel)."""
+    import paper_1801_00829_amd as F
+    monkeypatch.setenv("FUSE_CSR_STREAM", "0")
+    monkeypatch.setenv("FUSE_CSR_SCAP", scap)
+    m, n = 4000, 500
+    rp, ci, va = W.csr_bernoulli(m, n, 0.08, 95)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    (ky, ysp), ref_y = _sparse_side(m, n, 0.06, 96)                      # ~30 cells per row: over 8, under 64
+    (kz, zsp), ref_z = _sparse_side(m, n, 0.2, 97, rowptr64=True)        # ~100 cells per row: over both
+    xd = dev_csr(rp, ci, va, (m, n))
+    sd = dev_sides([(ky, ysp), (kz, zsp)])
+    expr = [("main",), ("side", 0), ("mul",), ("main",), ("side", 1), ("mul",), ("add",)]        # X*Y + X*Z
+    for agg in ("none", "row", "col", "full"):
+        got = host(F.fuse_cell_csr(expr, xd, sd, agg))
+        ref = unfused.cell_csr(expr, x, [ref_y, ref_z], agg)
+        a = np.abs(unfused.cell_csr(expr, x, [ref_y, ref_z], "none"))
+        scale = {"none": None, "full": a.sum(), "row": ops.csr_row_sums(x, a).max(initial=0.0),
+                 "col": ops.csr_col_sums(x, a).max(initial=0.0)}[agg]
+        assert_close(got, ref, scale=scale, what="sparse sides, %s LDS entries, %s" % (scap, agg))
+    assert ("#define FUSE_SCAP %s\n" % scap) in F.last_source()
+
+
 # ------------------------------------------- Row with a matrix right-hand side ---
 
 MLOG_Q = [("side", 1), ("main",), ("side", 0), ("matmult",), ("mul",)]                   # Q = P * (X V)
