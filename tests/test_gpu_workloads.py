@@ -119,6 +119,38 @@ def test_cell_variants_at_scale(sides_kind):
         assert_close(got, np.asarray(ref).reshape(-1), scale=scale, tol=TOL, what="cell %s %s" % (sides_kind, agg))
 
 
+def test_sparse_cell_with_sparse_sides_at_scale():
+    """Fig. 8b / 8d at 100000 x 1000 with X, Y and Z a tenth stored each (1e7 stored cells per matrix, the launch shape
+    of the large sweep sizes): sum(X*Y*Z) in all four variants and the two-aggregate MAgg, every output element against
+    the oracle's operator-at-a-time plan on the densified side matrices."""
+    import paper_1801_00829_amd as F
+    m, n = 100_000, 1000
+    rp, ci, va = W.csr_bernoulli(m, n, 0.1, 981)
+    x = ops.make_csr(rp, ci, va, (m, n))
+    gpu_sides, ref_sides = [], []
+    for seed, rp64 in ((982, False), (983, True)):
+        srp, sci, sva = W.csr_bernoulli(m, n, 0.1, seed)
+        gpu_sides.append(("sparse", (srp, sci, sva, (m, n), rp64)))
+        ref_sides.append(("matrix", ops.csr_to_dense(ops.make_csr(srp, sci, sva, (m, n)))))
+    xd, sd = dev_csr(rp, ci, va, (m, n)), dev_sides(gpu_sides)
+    expr = [("main",), ("side", 0), ("mul",), ("side", 1), ("mul",)]
+    none_ref = unfused.cell_csr(expr, x, ref_sides, "none")
+    absv = np.abs(none_ref)
+    for agg in ("none", "row", "col", "full"):
+        print("sparse cell with sparse sides at scale:", agg, flush=True)
+        got = host(F.fuse_cell_csr(expr, xd, sd, agg))
+        ref = none_ref if agg == "none" else unfused.cell_csr(expr, x, ref_sides, agg)
+        scale = None if agg == "none" else float(absv.sum()) if agg == "full" else \
+            float(ops.csr_row_sums(x, absv).max()) if agg == "row" else float(ops.csr_col_sums(x, absv).max())
+        assert_close(got, np.asarray(ref).reshape(-1), scale=scale, tol=TOL, what="sparse sides %s" % agg)
+    two = [[("main",), ("side", 0), ("mul",)], [("main",), ("side", 1), ("mul",)]]
+    got = host(F.fuse_magg_csr(two, xd, sd))
+    ref = unfused.magg_csr(two, x, ref_sides)
+    for j in range(2):
+        a = float(np.abs(unfused.cell_csr(two[j], x, ref_sides, "none")).sum())
+        assert_close(got[j], ref[j], scale=a, tol=TOL, what="sparse sides magg[%d]" % j)
+
+
 def test_long_chain_expression_at_scale():
     """The expression of the paper's instruction-footprint experiment (Sec. 5.3): sum(f(X / rowSums(X))) with f a
     chain of 31 scalar operations, on 30000 x 1000 (the oracle materialises every one of the 33 intermediates);
