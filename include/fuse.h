@@ -204,7 +204,8 @@ int fuse_magg_noalloc(const fuse_expr *exprs, int k, const fuse_dense *X, const 
 /* Cell and MAgg over a SPARSE main input (Fig. 8b / 8d; Sec. 5.2: the sparse
  * matrix X is the "sparse driver" that makes the whole operator sparse-safe).
  * The body is evaluated at the stored cells of the CSR matrix X only, with the
- * dense side inputs read at the same positions; it must be sparse-safe, i.e. be
+ * side inputs read at the same positions (dense sides by address, FUSE_SIDE_SPARSE
+ * sides by a search in the side's row: 0 where the side stores nothing); it must be sparse-safe, i.e. be
  * zero wherever X has no stored cell (products with X, zero-preserving unaries,
  * sums of such), otherwise FUSE_EDESC.
  *   fuse_cell_csr: agg NONE -> nnz values on X's pattern; ROW -> rows(X) sums;
