@@ -51,6 +51,25 @@ def profile_traffic(path=TRAFFIC_PROFILE):
     return out
 
 
+KERNEL_PROFILE = os.path.join(ROOT, "profiles", "bench_all_templates_kernel_stats.txt")
+
+
+def profile_kernel_us(path=KERNEL_PROFILE):
+    """Average duration (microseconds) of every kernel in the committed rocprofv3 kernel trace of this benchmark,
+    by kernel name (table rows `name calls total_ns avg_ns min_ns max_ns pct`).  Like the traffic figures, an entry
+    stands for exactly the code that was profiled: a kernel that has changed since has another name and no entry."""
+    out = {}
+    try:
+        with open(path) as f:
+            for line in f:
+                w = line.split()
+                if len(w) == 7 and w[0].startswith("fuse_") and w[6].endswith("%"):
+                    out[w[0]] = float(w[3]) / 1e3
+    except (OSError, ValueError):
+        pass
+    return out
+
+
 def seconds_at(nbytes, gbps_):
     """Time to move nbytes at gbps_ GB/s (1 GB = 1e9 bytes)."""
     return nbytes / (gbps_ * 1e9)
@@ -665,6 +684,7 @@ def main():
         del idx
 
     traffic = profile_traffic()
+    traced = profile_kernel_us()
     templates = {}
     for name in names:
         ts = sorted(a.elapsed_time(b) for a, b in ev[name])           # milliseconds
@@ -677,6 +697,13 @@ def main():
         e["traffic"] = None if tr is None else tr[0] + tr[1]
         if tr is not None:
             e["traffic_GBps"] = round(gbps(tr[0] + tr[1], avg * 1e-3), 1)
+        if kernels[name] in traced:
+            # the kernel's own duration in the committed kernel trace (the event bracket above also holds the two
+            # event records and, for Row and Outer, the small second kernel of a call)
+            e["profiled_kernel_us"] = round(traced[kernels[name]], 2)
+            if name != "outer":
+                e["profiled_kernel_frac_of_hbm_peak"] = round(
+                    gbps(info[name]["bytes"], traced[kernels[name]] * 1e-6) / HBM_PEAK_GBPS, 4)
         if info[name]["nnz"]:
             e["nnz_per_s"] = float("%.5g" % (info[name]["nnz"] / (avg * 1e-3)))
         if name == "outer":
