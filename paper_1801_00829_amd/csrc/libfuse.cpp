@@ -814,8 +814,11 @@ int cell_impl(const fuse_expr *exprs, int k, const fuse_dense *X, const fuse_sid
     for (int q = 0; q < nsides; ++q)
         nmat += prog.side_used[q] && sides[q].kind == FUSE_SIDE_MATRIX;
     int UNROLL = env_int("FUSE_CELL_UNROLL", 0);
+    // vectors per thread and input in flight.  Measured (1e5 .. 1e6 x 1000): one input 8; two inputs 4 (X*Y full_agg
+    // 225 us against 232 with 8, no_agg 424 against 441); three inputs and a full aggregate 8 (the 2.4 GB MAgg
+    // workload 339 us against 348 with 4 and 352 with 16; sum(X*Y*Z) on 24 GB 3.39 against 3.45 ms)
     if (UNROLL <= 0)
-        UNROLL = nmat <= 1 ? 8 : (nmat <= 4 ? 4 : 2);
+        UNROLL = nmat <= 1 ? 8 : (nmat == 3 && ac == 1) ? 8 : (nmat <= 4 ? 4 : 2);
     // threads per block (FUSE_CELL_BLOCK: 256, 512 or 1024; 0 = by rule)
     int CBLOCK = env_int("FUSE_CELL_BLOCK", 0);
     if (CBLOCK != 256 && CBLOCK != 512 && CBLOCK != 1024)
