@@ -556,19 +556,20 @@ def main():
     print("# warm-up %.1f s (hipRTC %.0f ms for %d plans)" % (time.perf_counter() - t0, compile_ms, misses),
           file=sys.stderr, flush=True)
 
-    # ---- timed region: exactly K steps; HIP events on the launch stream around every operator
+    # ---- timed region: exactly K steps; HIP events on the launch stream between the operators (one event is the
+    # end of an operator and the start of the next).  An operator's time between its two events also holds the
+    # queue's handling of an event packet: ~4 us, which only shows in the 8 us Cell operator.
     K = args.steps
-    ev = {n: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
-          for n in names}
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(K):
-        for name in names:
-            a, b = ev[name][k]
-            a.record()
+        marks[k][0].record()
+        for i, name in enumerate(names):
             calls[name]()
-            b.record()
+            marks[k][i + 1].record()
     torch.cuda.synchronize()
+    ev = {name: [(marks[k][i], marks[k][i + 1]) for k in range(K)] for i, name in enumerate(names)}
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / K * 1e3
 
