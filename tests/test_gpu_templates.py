@@ -869,7 +869,7 @@ def _sparse_side(m, n, dens, seed, rowptr64=False):
     return ("sparse", (rp, ci, va, (m, n), rowptr64)), ("matrix", dense)
 
 
-@pytest.mark.parametrize("case", range(10 * MORE))
+@pytest.mark.parametrize("case", range(5 * MORE))
 def test_sparse_side_inputs_random_expressions(case, csr_mapping):
     """Cell, MAgg and Row bodies over a CSR main input whose matrix side input is sparse as well (Table 1: sparse /
     dense side inputs; Fig. 8b / 8d): every result against the oracle's operator-at-a-time plan on the densified side."""
