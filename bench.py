@@ -168,7 +168,7 @@ def sweep(args):
         if g not in SWEEP_GROUPS:
             sys.exit("unknown sweep group %r (known: %s)" % (g, ", ".join(SWEEP_GROUPS)))
     n = 1000
-    rows = [x for x in (1000, 10_000, 100_000, 1_000_000) if x <= args.max_rows]
+    rows = [x for x in (1000, 10_000, 100_000, 1_000_000) if args.min_rows <= x <= args.max_rows]
 
     def timed(fn, warm=2):
         for _ in range(warm):
@@ -461,6 +461,7 @@ def main():
                     help="timing sweep over the paper's micro-benchmark sizes instead of the benchmark line "
                          "(comma-separated groups, see sweep(); default all)")
     ap.add_argument("--max-rows", type=int, default=1_000_000, help="--sweep: largest number of rows of the Fig. 8 groups")
+    ap.add_argument("--min-rows", type=int, default=1000, help="--sweep: smallest number of rows of the Fig. 8 groups")
     ap.add_argument("--iters", type=int, default=7, help="--sweep: timed calls per point (median reported)")
     ap.add_argument("--cell-budget", action="store_true",
                     help="time budget of the 24 MB Cell workload instead of the benchmark line (see cell_budget())")
