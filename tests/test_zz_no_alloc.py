@@ -52,6 +52,41 @@ def test_noalloc_magg_matches_fuse_magg_on_two_calls_in_a_row():
             assert np.array_equal(host(o), w) and np.array_equal(host(o3), w3), rep
 
 
+def test_noalloc_magg_recorded_into_a_hip_graph():
+    """What the entry point is for: a caller under stream capture.  Two calls (a large and a small input) are recorded
+    into one HIP graph after one eager call each; the graph is replayed three times with the inputs changed in
+    between (and eager work on the same operators between the replays), every replay against the eager result."""
+    import torch
+    import paper_1801_00829_amd as F
+    big, small = _inputs(2003, 1000, 21), _inputs(129, 1000, 22)
+    dev = [(to_dev(x), dev_sides([("matrix", y), ("matrix", z)])) for x, y, z in (big, small)]
+    out = [torch.zeros(3, dtype=torch.float64, device="cuda") for _ in dev]
+    gs = torch.cuda.Stream()
+    gs.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(gs):
+        for (x, s), o in zip(dev, out):
+            F.fuse_magg(MAGG, x, s)                                    # compiled and loaded; the per-device set-up done
+            F.fuse_magg_noalloc(MAGG, x, s, o)
+    gs.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=gs):
+        for (x, s), o in zip(dev, out):
+            F.fuse_magg_noalloc(MAGG, x, s, o)
+    for rep in range(3):
+        for (x, s) in dev:                                             # new values in the same buffers
+            x.mul_(1.0 + 0.125 * (rep + 1))
+            s[0][1].add_(0.25)
+        torch.cuda.synchronize()
+        for o in out:
+            o.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        got = [host(o).copy() for o in out]
+        want = [host(F.fuse_magg(MAGG, x, s)).copy() for x, s in dev]  # eager, between the replays
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b), (rep, a, b)
+
+
 def test_noalloc_magg_refuses_what_it_cannot_do_without_allocating():
     import torch
     import paper_1801_00829_amd as F
